@@ -1,0 +1,145 @@
+/*
+ * moe_gfx950 -- forward pass of the position-wise top-2 Mixture-of-Experts layer
+ * of GShard (arXiv 2006.16668) on one AMD MI355X (gfx950), one device's share of
+ * tokens.  C ABI; every step runs in hand-written HIP kernels.
+ *
+ * Notation (paper, Section 2.2 and 3.1):
+ *   G groups, S tokens per group, M model dimension, H expert hidden dimension,
+ *   E experts, C capacity of one expert inside one group.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
+ *     contiguous, 16-byte aligned.  The config struct is a HOST pointer.
+ *   - The library allocates nothing, frees nothing, never synchronises the
+ *     device and keeps no state between calls.  Scratch memory comes from the
+ *     caller's workspace (size: moe_workspace_bytes / moe_gate_workspace_bytes).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns immediately.
+ *   - Return value: MOE_OK or a negative moe_status.  Nothing is enqueued when
+ *     an argument check fails.  No exception or abort crosses the boundary.
+ *   - Activations / expert weights / buffers have the element type
+ *     cfg->act_dtype (fp32 or bf16).  The gate path (wg, u, gates, weights,
+ *     auxiliary loss) is always fp32.  bf16 expert GEMMs accumulate in fp32; the
+ *     hidden activation h is rounded to bf16 once.
+ *
+ * Slot codes in `slot[G,S,2]`:  >= 0  position c in the expert's buffer;
+ *   MOE_SLOT_OVERFLOW (-1) expert already full (Section 2.2, "Expert capacity");
+ *   MOE_SLOT_NOT_SAMPLED (-2) second expert skipped by random routing
+ *   (Section 2.2, "Random routing"); it takes precedence over -1.
+ */
+#ifndef MOE_GFX950_H
+#define MOE_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_EINVAL = -1,       /* null / misaligned pointer, non-positive dimension, E < 2, C < 1 */
+  MOE_EUNSUPPORTED = -2, /* a shape the kernels do not tile (see moe_expert_ffn) */
+  MOE_EWORKSPACE = -3,   /* workspace too small */
+  MOE_EHIP = -4          /* a kernel launch failed; hipGetLastError() is left for the caller */
+} moe_status;
+
+#define MOE_SLOT_OVERFLOW (-1)
+#define MOE_SLOT_NOT_SAMPLED (-2)
+
+typedef struct {
+  int32_t G, S, M, H, E, C;
+  int32_t act_dtype; /* moe_dtype */
+} moe_config;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* moe_status_string(int status);
+
+/* Bytes of workspace moe_gate needs for this config.  Pure host function. */
+int moe_gate_workspace_bytes(const moe_config* cfg, size_t* bytes);
+
+/* Bytes of workspace moe_forward needs (routing tensors, expert buffers and the
+ * gate scratch).  Pure host function. */
+int moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
+
+/*
+ * Top2Gating: Algorithm 1 of the paper for G independent groups (Section 2.2,
+ * "Local group dispatching") and line 1 of Algorithm 2 (gate softmax).
+ *
+ *   g[g,s,:]   = softmax_e( sum_m x[g,s,m] wg[m,e] )
+ *   (e1,e2)    = indices of the largest and second largest gate (ties: lowest index)
+ *   pass 1     : token s takes position #{s'<s : e1[s']=e1[s]} of expert e1,
+ *                kept when the position is < C; weight g1/(g1+g2)
+ *   l_aux[g]   = (1/E) sum_e (c1[g,e]/S) mean_gate[g,e],  c1 = first-choice counts
+ *                (all tokens, also overflowing ones), mean_gate = mean over s of g
+ *   pass 2     : second choice sampled iff 2*g2/(g1+g2) > u[g,s]; a sampled token
+ *                takes position c1[g,e2] + #{s'<s sampled : e2[s']=e2[s]}, kept when
+ *                < C; weight g2/(g1+g2).  A non-sampled second choice consumes no
+ *                capacity.
+ *
+ * in : x [G,S,M] act_dtype;  wg [M,E] fp32;  u [G,S] fp32 uniforms in [0,1)
+ * out: expert_idx [G,S,2] i32;  slot [G,S,2] i32 (codes above);
+ *      weight [G,S,2] fp32 combine weight, 0 when the choice is not kept;
+ *      fill [G,E] i32 occupied slots;  src_token [E,G,C] i32 inverse map
+ *      slot -> s (the gather indices of Section 3.2's gather-based dispatch), -1 empty;
+ *      c1 [G,E] i32;  mean_gate [G,E] fp32;  aux [G] fp32;
+ *      gates_opt [G,S,E] fp32 or NULL (full softmax output, for inspection)
+ * ws : at least moe_gate_workspace_bytes(cfg)
+ */
+int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float* u,
+             int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
+             int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
+             float* gates_opt, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dispatch (Algorithm 2, the GSEC,GSM->EGCM einsum, computed as the gather of
+ * Section 3.2):  buf[e,g,c,:] = x[g, src_token[e,g,c], :], zeros where
+ * src_token is -1.
+ * in : x [G,S,M];  src_token [E,G,C]        out: buf [E,G,C,M] act_dtype
+ */
+int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token,
+                 void* buf, void* stream);
+
+/*
+ * Expert networks (Eq. 2; Algorithm 2, EGCM,EMH->EGCH, relu, EGCH,EHM->EGCM):
+ *   h[e]   = relu( buf[e] . wi[e] )        [G*C, M] x [M, H]
+ *   out[e] = h[e] . wo[e]                  [G*C, H] x [H, M]
+ * Rows of buf are processed whether occupied or not (an empty row is zero and
+ * FFN_e(0) = 0 since the experts have no bias).  The output keeps the EGCM
+ * order on one device (the paper prints GECM, its layout after the reverse
+ * exchange between devices).
+ * in : buf [E,G,C,M];  wi [E,M,H];  wo [E,H,M]   (act_dtype)
+ * tmp: h_ws [E,G,C,H] act_dtype (caller-provided scratch)
+ * out: out [E,G,C,M] act_dtype
+ * bf16 requires M % 8 == 0 and H % 8 == 0 (16-byte rows), else MOE_EUNSUPPORTED.
+ */
+int moe_expert_ffn(const moe_config* cfg, const void* buf, const void* wi, const void* wo,
+                   void* h_ws, void* out, void* stream);
+
+/*
+ * Combine (Eq. 3; Algorithm 2, the GSEC,EGCM->GSM einsum, computed as a gather):
+ *   y[g,s,:] = sum_{k: slot[g,s,k] >= 0} weight[g,s,k] * out[expert_idx[g,s,k], g, slot[g,s,k], :]
+ * A token with no kept choice gets a zero row (Section 2.2: overflowed tokens).
+ * Accumulation in fp32, one rounding to act_dtype.
+ */
+int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_idx,
+                const int32_t* slot, const float* weight, void* y, void* stream);
+
+/*
+ * The whole layer forward (Algorithm 2): gate -> dispatch -> experts -> combine.
+ * in : x [G,S,M], wg [M,E], u [G,S], wi [E,M,H], wo [E,H,M]
+ * out: y [G,S,M] act_dtype;  aux [G] fp32 (per-group auxiliary loss)
+ * ws : at least moe_workspace_bytes(cfg); all routing tensors and expert buffers
+ *      live there and are overwritten by every call.
+ */
+int moe_forward(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                const void* wi, const void* wo, void* y, float* aux,
+                void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_GFX950_H */

@@ -1,0 +1,14 @@
+"""MI355X-native forward pass of GShard's top-2 Mixture-of-Experts layer.
+
+``binding`` holds thin ctypes wrappers around the C ABI declared in
+``include/moe_gfx950.h``; every step of the layer runs in the HIP kernels of
+``libmoe_gfx950.so`` (built by ``python -m paper_2006_16668_amd.build``).
+There is no CPU fallback: a missing library raises on first use.
+"""
+from .binding import (MoEError, MoEShape, library_path, load_library, moe_combine, moe_dispatch,
+                      moe_expert_ffn, moe_forward, moe_gate, moe_gate_workspace_bytes,
+                      moe_status_string, moe_workspace_bytes)
+
+__all__ = ["MoEError", "MoEShape", "library_path", "load_library", "moe_combine", "moe_dispatch",
+           "moe_expert_ffn", "moe_forward", "moe_gate", "moe_gate_workspace_bytes",
+           "moe_status_string", "moe_workspace_bytes"]

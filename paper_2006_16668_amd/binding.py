@@ -1,0 +1,196 @@
+"""ctypes binding of libmoe_gfx950.so: argument marshalling only.
+
+The functions have the names and argument order of the C ABI.  Tensors are torch
+tensors on the GPU (torch serves as allocator and stream provider); the wrappers
+check dtype / shape / contiguity, pass ``data_ptr()`` and the current stream,
+and raise ``MoEError`` on a negative status.  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libmoe_gfx950.so"
+_lib = None
+
+MOE_F32, MOE_BF16 = 0, 1
+SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
+
+EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
+           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward")
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {moe_status_string(status)} ({status})")
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("G", "S", "M", "H", "E", "C", "act_dtype")]
+
+
+@dataclass(frozen=True)
+class MoEShape:
+    """G groups, S tokens per group, M model dim, H hidden dim, E experts, C capacity."""
+    G: int
+    S: int
+    M: int
+    H: int
+    E: int
+    C: int
+    act_dtype: str = "bf16"   # "f32" | "bf16"
+
+    @property
+    def torch_dtype(self):
+        return {"f32": torch.float32, "bf16": torch.bfloat16}[self.act_dtype]
+
+    def _c(self) -> _Config:
+        return _Config(self.G, self.S, self.M, self.H, self.E, self.C,
+                       {"f32": MOE_F32, "bf16": MOE_BF16}[self.act_dtype])
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2006_16668_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    cfgp = ctypes.POINTER(_Config)
+    lib.moe_status_string.restype = ctypes.c_char_p
+    lib.moe_status_string.argtypes = [i32]
+    for name, args in {
+        "moe_gate_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_gate": [cfgp] + [vp] * 13 + [sz, vp],
+        "moe_dispatch": [cfgp, vp, vp, vp, vp],
+        "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
+        "moe_combine": [cfgp, vp, vp, vp, vp, vp, vp],
+        "moe_forward": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+    }.items():
+        fn = getattr(lib, name)
+        fn.restype = i32
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def moe_status_string(status: int) -> str:
+    return load_library().moe_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MoEError(status, where)
+
+
+def _ptr(t, dtype, shape, name):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ws(ws, name="ws"):
+    if not isinstance(ws, torch.Tensor) or not ws.is_cuda or ws.dtype != torch.uint8 \
+            or not ws.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous uint8 GPU tensor")
+    return ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def moe_gate_workspace_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_gate_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
+           "moe_gate_workspace_bytes")
+    return n.value
+
+
+def moe_workspace_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
+           "moe_workspace_bytes")
+    return n.value
+
+
+def moe_gate(shape: MoEShape, x, wg, u, expert_idx, slot, weight, fill, src_token, c1, mean_gate,
+             aux, gates_opt, ws):
+    G, S, M, E, C = shape.G, shape.S, shape.M, shape.E, shape.C
+    i32, f32 = torch.int32, torch.float32
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_gate(
+        ctypes.byref(c), _ptr(x, shape.torch_dtype, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"),
+        _ptr(u, f32, (G, S), "u"), _ptr(expert_idx, i32, (G, S, 2), "expert_idx"),
+        _ptr(slot, i32, (G, S, 2), "slot"), _ptr(weight, f32, (G, S, 2), "weight"),
+        _ptr(fill, i32, (G, E), "fill"), _ptr(src_token, i32, (E, G, C), "src_token"),
+        _ptr(c1, i32, (G, E), "c1"), _ptr(mean_gate, f32, (G, E), "mean_gate"),
+        _ptr(aux, f32, (G,), "aux"), _ptr(gates_opt, f32, (G, S, E), "gates_opt"),
+        wsp, wsn, _stream()), "moe_gate")
+
+
+def moe_dispatch(shape: MoEShape, x, src_token, buf):
+    G, S, M, E, C = shape.G, shape.S, shape.M, shape.E, shape.C
+    c = shape._c()
+    _check(load_library().moe_dispatch(
+        ctypes.byref(c), _ptr(x, shape.torch_dtype, (G, S, M), "x"),
+        _ptr(src_token, torch.int32, (E, G, C), "src_token"),
+        _ptr(buf, shape.torch_dtype, (E, G, C, M), "buf"), _stream()), "moe_dispatch")
+
+
+def moe_expert_ffn(shape: MoEShape, buf, wi, wo, h_ws, out):
+    G, M, H, E, C = shape.G, shape.M, shape.H, shape.E, shape.C
+    dt = shape.torch_dtype
+    c = shape._c()
+    _check(load_library().moe_expert_ffn(
+        ctypes.byref(c), _ptr(buf, dt, (E, G, C, M), "buf"), _ptr(wi, dt, (E, M, H), "wi"),
+        _ptr(wo, dt, (E, H, M), "wo"), _ptr(h_ws, dt, (E, G, C, H), "h_ws"),
+        _ptr(out, dt, (E, G, C, M), "out"), _stream()), "moe_expert_ffn")
+
+
+def moe_combine(shape: MoEShape, out, expert_idx, slot, weight, y):
+    G, S, M, E, C = shape.G, shape.S, shape.M, shape.E, shape.C
+    dt = shape.torch_dtype
+    c = shape._c()
+    _check(load_library().moe_combine(
+        ctypes.byref(c), _ptr(out, dt, (E, G, C, M), "out"),
+        _ptr(expert_idx, torch.int32, (G, S, 2), "expert_idx"),
+        _ptr(slot, torch.int32, (G, S, 2), "slot"), _ptr(weight, torch.float32, (G, S, 2), "weight"),
+        _ptr(y, dt, (G, S, M), "y"), _stream()), "moe_combine")
+
+
+def moe_forward(shape: MoEShape, x, wg, u, wi, wo, y, aux, ws):
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    dt, f32 = shape.torch_dtype, torch.float32
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_forward(
+        ctypes.byref(c), _ptr(x, dt, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"),
+        _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
+        _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream()),
+        "moe_forward")

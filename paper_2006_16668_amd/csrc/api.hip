@@ -1,0 +1,156 @@
+// C ABI of the library: argument checks, workspace carving, kernel sequencing.
+// Every step of the layer runs in the kernels of gate.hip, dispatch_combine.hip
+// and expert_gemm.hip; nothing here computes.
+#include "common.h"
+
+namespace {
+
+using moe::align_up;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_config(const moe_config* c) {
+  if (c == nullptr) return MOE_EINVAL;
+  if (c->G < 1 || c->S < 1 || c->M < 1 || c->H < 1 || c->E < 2 || c->C < 1) return MOE_EINVAL;
+  if (c->act_dtype != MOE_F32 && c->act_dtype != MOE_BF16) return MOE_EINVAL;
+  // rows are moved and multiplied in 16-byte pieces
+  if (c->M % 8 != 0 || c->H % 8 != 0) return MOE_EUNSUPPORTED;
+  if ((long long)c->G * c->S > 0x3fffffffLL) return MOE_EUNSUPPORTED;
+  if ((long long)c->E * c->G * c->C > 0x7fffffffLL) return MOE_EUNSUPPORTED;
+  return MOE_OK;
+}
+
+// Layout of the moe_forward workspace.
+struct ForwardWs {
+  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, buf, h, out, gate_ws, total;
+};
+
+ForwardWs carve(const moe_config& c) {
+  const size_t N = (size_t)c.G * c.S, GE = (size_t)c.G * c.E, rows = (size_t)c.E * c.G * c.C;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  ForwardWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.expert_idx = take(N * 2 * 4);
+  w.slot = take(N * 2 * 4);
+  w.weight = take(N * 2 * 4);
+  w.fill = take(GE * 4);
+  w.src_token = take(rows * 4);
+  w.c1 = take(GE * 4);
+  w.mean_gate = take(GE * 4);
+  w.buf = take(rows * c.M * elt);
+  w.h = take(rows * c.H * elt);
+  w.out = take(rows * c.M * elt);
+  w.gate_ws = take(moe::gate_workspace_bytes(c));
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "MOE_OK";
+    case MOE_EINVAL: return "MOE_EINVAL: invalid argument";
+    case MOE_EUNSUPPORTED: return "MOE_EUNSUPPORTED: shape not supported by the kernels";
+    case MOE_EWORKSPACE: return "MOE_EWORKSPACE: workspace too small";
+    case MOE_EHIP: return "MOE_EHIP: kernel launch failed";
+    default: return "unknown moe_status";
+  }
+}
+
+int moe_gate_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = moe::gate_workspace_bytes(*cfg);
+  return MOE_OK;
+}
+
+int moe_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve(*cfg).total;
+  return MOE_OK;
+}
+
+int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float* u,
+             int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
+             int32_t* src_token, int32_t* c1, float* mean_gate, float* aux, float* gates_opt,
+             void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, wg, u, expert_idx, slot, weight, fill, src_token, c1, mean_gate, aux, ws};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
+  if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
+  return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
+                          mean_gate, aux, gates_opt, ws, static_cast<hipStream_t>(stream));
+}
+
+int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token, void* buf,
+                 void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, src_token, buf};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  return moe::launch_dispatch(*cfg, x, src_token, buf, static_cast<hipStream_t>(stream));
+}
+
+int moe_expert_ffn(const moe_config* cfg, const void* buf, const void* wi, const void* wo,
+                   void* h_ws, void* out, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {buf, wi, wo, h_ws, out};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  return moe::launch_expert_ffn(*cfg, buf, wi, wo, h_ws, out, static_cast<hipStream_t>(stream));
+}
+
+int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_idx,
+                const int32_t* slot, const float* weight, void* y, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {out, expert_idx, slot, weight, y};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  return moe::launch_combine(*cfg, out, expert_idx, slot, weight, y,
+                             static_cast<hipStream_t>(stream));
+}
+
+int moe_forward(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
+                void* stream) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, wg, u, wi, wo, y, aux, ws};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  const ForwardWs w = carve(*cfg);
+  if (ws_bytes < w.total) return MOE_EWORKSPACE;
+  char* base = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t* expert_idx = reinterpret_cast<int32_t*>(base + w.expert_idx);
+  int32_t* slot = reinterpret_cast<int32_t*>(base + w.slot);
+  float* weight = reinterpret_cast<float*>(base + w.weight);
+  int32_t* src_token = reinterpret_cast<int32_t*>(base + w.src_token);
+  rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
+                        reinterpret_cast<int32_t*>(base + w.fill), src_token,
+                        reinterpret_cast<int32_t*>(base + w.c1),
+                        reinterpret_cast<float*>(base + w.mean_gate), aux, nullptr,
+                        base + w.gate_ws, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_expert_ffn(*cfg, base + w.buf, wi, wo, base + w.h, base + w.out, st);
+  if (rc != MOE_OK) return rc;
+  return moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Dispatch and combine of Algorithm 2, computed as row gathers instead of the
+// one-hot einsums (the gather form is the one Section 3.2 sketches):
+//
+//   dispatch: buf[e,g,c,:] = x[g, src_token[e,g,c], :]       (zeros for empty slots)
+//   combine : y[g,s,:]     = sum_k weight[g,s,k] * out[e_k, g, slot_k, :]
+//
+// Both are pure HBM traffic: one wavefront moves one row with 16-byte accesses.
+#include "common.h"
+
+namespace moe {
+namespace {
+
+constexpr int kRowsPerBlock = 4;  // one wavefront per row
+
+// rows are M*sizeof(T) bytes, a multiple of 16
+__global__ __launch_bounds__(256) void dispatch_kernel(
+    const uint4* __restrict__ x, const int32_t* __restrict__ src_token, uint4* __restrict__ buf,
+    int S, int G, int C, int vec_per_row, long long rows) {
+  const long long r = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int g = (int)((r / C) % G);
+  const int t = src_token[r];
+  uint4* dst = buf + r * vec_per_row;
+  if (t >= 0) {
+    const uint4* src = x + ((long long)g * S + t) * vec_per_row;
+    for (int v = lane; v < vec_per_row; v += 64) dst[v] = src[v];
+  } else {
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    for (int v = lane; v < vec_per_row; v += 64) dst[v] = zero;
+  }
+}
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int kElts = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return uint4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                 __float_as_uint(f[3])};
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int kElts = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return uint4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                 pack_bf16x2(f[6], f[7])};
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(
+    const uint4* __restrict__ out, const int32_t* __restrict__ expert_idx,
+    const int32_t* __restrict__ slot, const float* __restrict__ weight, uint4* __restrict__ y,
+    int S, int G, int C, int vec_per_row, long long tokens) {
+  const long long n = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (n >= tokens) return;
+  const int lane = threadIdx.x & 63;
+  const int g = (int)(n / S);
+  const int s0 = slot[2 * n], s1 = slot[2 * n + 1];
+  const float w0 = weight[2 * n], w1 = weight[2 * n + 1];
+  const uint4* r0 = s0 >= 0 ? out + (((long long)expert_idx[2 * n] * G + g) * C + s0) * vec_per_row : nullptr;
+  const uint4* r1 = s1 >= 0 ? out + (((long long)expert_idx[2 * n + 1] * G + g) * C + s1) * vec_per_row : nullptr;
+  uint4* dst = y + n * vec_per_row;
+  constexpr int K = Vec16<T>::kElts;
+  for (int v = lane; v < vec_per_row; v += 64) {
+    float acc[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) acc[i] = 0.f;
+    if (r0 != nullptr) {
+      float f[K];
+      Vec16<T>::unpack(r0[v], f);
+#pragma unroll
+      for (int i = 0; i < K; ++i) acc[i] = w0 * f[i];
+    }
+    if (r1 != nullptr) {
+      float f[K];
+      Vec16<T>::unpack(r1[v], f);
+#pragma unroll
+      for (int i = 0; i < K; ++i) acc[i] = fmaf(w1, f[i], acc[i]);
+    }
+    dst[v] = Vec16<T>::pack(acc);
+  }
+}
+
+}  // namespace
+
+int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token, void* buf,
+                    hipStream_t st) {
+  const int elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  const int vec_per_row = c.M * elt / 16;
+  const long long rows = (long long)c.E * c.G * c.C;
+  const unsigned grid = (unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL(dispatch_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint4*>(x),
+                     src_token, static_cast<uint4*>(buf), c.S, c.G, c.C, vec_per_row, rows);
+  return check_launch();
+}
+
+int launch_combine(const moe_config& c, const void* out, const int32_t* expert_idx,
+                   const int32_t* slot, const float* weight, void* y, hipStream_t st) {
+  const int elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  const int vec_per_row = c.M * elt / 16;
+  const long long tokens = (long long)c.G * c.S;
+  const unsigned grid = (unsigned)((tokens + kRowsPerBlock - 1) / kRowsPerBlock);
+  if (c.act_dtype == MOE_F32)
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(grid), dim3(256), 0, st,
+                       static_cast<const uint4*>(out), expert_idx, slot, weight,
+                       static_cast<uint4*>(y), c.S, c.G, c.C, vec_per_row, tokens);
+  else
+    hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(grid), dim3(256), 0, st,
+                       static_cast<const uint4*>(out), expert_idx, slot, weight,
+                       static_cast<uint4*>(y), c.S, c.G, c.C, vec_per_row, tokens);
+  return check_launch();
+}
+
+}  // namespace moe

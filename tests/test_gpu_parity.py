@@ -1,0 +1,155 @@
+"""HIP path against the fp64 oracle, element by element, through the C ABI.
+
+Tolerances: integer routing bit-exact; gates / weights / auxiliary loss 1e-5
+relative (fp32 arithmetic, fp64 oracle); expert and layer outputs 2e-2 relative
+in the Frobenius norm with bf16 experts, 1e-5 with fp32 experts.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_16668_amd as moe
+from oracle import moe_oracle as orc
+from workloads import CONFIGS, ExpertWeightsF64, MoEConfig, make_inputs
+
+from harness import (assert_gate_floats_close, assert_routing_equal, f64, gpu_forward, gpu_gate,
+                     rel_fro, shape_of)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+OUT_TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+# several tiles and ragged tails: S not a multiple of the 64-token chunk, M / H not
+# multiples of the 64-wide K step, rows per expert not a multiple of the GEMM tile
+SMALL_CASES = [
+    CONFIGS["tiny"],
+    CONFIGS["small"],
+    MoEConfig("ragged_bf16", G=3, S=200, M=72, H=136, E=5, C=37, act_dtype="bf16", seed=11),
+    MoEConfig("ragged_f32", G=2, S=131, M=40, H=88, E=7, C=50, act_dtype="f32", seed=12),
+    MoEConfig("e130", G=2, S=300, M=64, H=64, E=130, C=6, act_dtype="bf16", seed=13),
+    MoEConfig("two_experts", G=2, S=96, M=32, H=48, E=2, C=96, act_dtype="f32", seed=14),
+    MoEConfig("capacity_one", G=4, S=70, M=32, H=32, E=6, C=1, act_dtype="bf16", seed=15),
+    MoEConfig("one_token", G=5, S=1, M=16, H=24, E=3, C=2, act_dtype="f32", seed=16),
+    MoEConfig("wide_rows", G=2, S=520, M=256, H=520, E=3, C=300, act_dtype="bf16", seed=17),
+]
+
+
+def _oracle_layer(cfg, inp):
+    x, wg, u = inp.host_f64()
+    return orc.moe_forward(x, wg, u, ExpertWeightsF64(inp.wi), ExpertWeightsF64(inp.wo), cfg.C)
+
+
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_stages_and_layer_match_oracle(cfg):
+    print(f"case {cfg}", flush=True)
+    inp = make_inputs(cfg, device=DEV)
+    y_want, want, buf_want, out_want = _oracle_layer(cfg, inp)
+    sh = shape_of(cfg)
+
+    # --- gating
+    r = gpu_gate(cfg, inp.x, inp.wg, inp.u)
+    assert_routing_equal(r, want)
+    assert_gate_floats_close(r, want, gates=want["gates"])
+
+    # --- dispatch: a copy, so exact
+    buf = torch.full((cfg.E, cfg.G, cfg.C, cfg.M), float("nan"), dtype=sh.torch_dtype, device=DEV)
+    moe.moe_dispatch(sh, inp.x, r["src_token"], buf)
+    torch.cuda.synchronize()
+    assert np.array_equal(f64(buf), buf_want)
+
+    # --- experts
+    h = torch.empty((cfg.E, cfg.G, cfg.C, cfg.H), dtype=sh.torch_dtype, device=DEV)
+    out = torch.full((cfg.E, cfg.G, cfg.C, cfg.M), float("nan"), dtype=sh.torch_dtype, device=DEV)
+    moe.moe_expert_ffn(sh, buf, inp.wi, inp.wo, h, out)
+    torch.cuda.synchronize()
+    tol = OUT_TOL[cfg.act_dtype]
+    assert rel_fro(f64(out), out_want) < tol
+    # per occupied row as well, so a single broken row cannot hide in the norm
+    occ = want["src_token"] >= 0
+    if occ.any():
+        got_rows, want_rows = f64(out)[occ], out_want[occ]
+        row_err = np.linalg.norm(got_rows - want_rows, axis=1) / np.maximum(
+            np.linalg.norm(want_rows, axis=1), 1e-30)
+        assert row_err.max() < 4 * tol, row_err.max()
+    assert (f64(out)[~occ] == 0).all()                 # FFN_e(0) = 0
+
+    # --- combine on the GPU's own expert outputs
+    y = torch.full((cfg.G, cfg.S, cfg.M), float("nan"), dtype=sh.torch_dtype, device=DEV)
+    moe.moe_combine(sh, out, r["expert_idx"], r["slot"], r["weight"], y)
+    torch.cuda.synchronize()
+    assert rel_fro(f64(y), y_want) < tol
+    dropped = (want["slot"] < 0).all(axis=-1)
+    assert (f64(y)[dropped] == 0).all()                # fully dropped token -> zero row
+
+    # --- fused entry point gives the same bits as the staged calls
+    y2, aux2 = gpu_forward(cfg, inp)
+    assert torch.equal(y2, y)
+    assert torch.equal(aux2, r["aux"])
+
+
+def test_combine_is_exact_gather_for_identity_like_inputs():
+    """Dispatch then combine with out := buf: y = (w0 + w1) x up to one rounding."""
+    cfg = MoEConfig("roundtrip", G=2, S=150, M=64, H=64, E=4, C=80, act_dtype="f32", seed=21)
+    inp = make_inputs(cfg, device=DEV)
+    sh = shape_of(cfg)
+    r = gpu_gate(cfg, inp.x, inp.wg, inp.u)
+    buf = torch.empty((cfg.E, cfg.G, cfg.C, cfg.M), dtype=torch.float32, device=DEV)
+    moe.moe_dispatch(sh, inp.x, r["src_token"], buf)
+    y = torch.empty_like(inp.x)
+    moe.moe_combine(sh, buf, r["expert_idx"], r["slot"], r["weight"], y)
+    torch.cuda.synchronize()
+    wsum = f64(r["weight"]).sum(-1, keepdims=True)
+    np.testing.assert_allclose(f64(y), wsum * f64(inp.x), rtol=3e-7, atol=1e-30)
+
+
+def test_zero_gate_weights_tie_break_and_closed_form_aux():
+    """wg = 0: every token ties; lowest indices win, expert 0 keeps the first C tokens,
+    l_aux = 1/E^2 (closed form)."""
+    cfg = MoEConfig("ties", G=2, S=100, M=32, H=32, E=8, C=10, act_dtype="bf16", seed=22)
+    inp = make_inputs(cfg, device=DEV, condition=False)
+    wg = torch.zeros_like(inp.wg)
+    u = torch.zeros_like(inp.u)
+    r = gpu_gate(cfg, inp.x, wg, u)
+    idx = r["expert_idx"].cpu().numpy()
+    assert (idx[..., 0] == 0).all() and (idx[..., 1] == 1).all()
+    slot = r["slot"].cpu().numpy()
+    want = np.where(np.arange(cfg.S) < cfg.C, np.arange(cfg.S), -1)
+    assert (slot[..., 0] == want).all() and (slot[..., 1] == want).all()
+    np.testing.assert_allclose(f64(r["aux"]), 1.0 / cfg.E ** 2, rtol=1e-6)
+    np.testing.assert_allclose(f64(r["gates"]), 1.0 / cfg.E, rtol=1e-6)
+
+
+def test_results_are_deterministic():
+    cfg = CONFIGS["small"]
+    inp = make_inputs(cfg, device=DEV)
+    y1, a1 = gpu_forward(cfg, inp)
+    y2, a2 = gpu_forward(cfg, inp)
+    assert torch.equal(y1, y2) and torch.equal(a1, a2)
+    r1 = gpu_gate(cfg, inp.x, inp.wg, inp.u)
+    r2 = gpu_gate(cfg, inp.x, inp.wg, inp.u)
+    for k in r1:
+        assert torch.equal(r1[k], r2[k]), k
+
+
+def test_argument_errors_enqueue_nothing():
+    cfg = CONFIGS["tiny"]
+    inp = make_inputs(cfg, device=DEV)
+    sh = shape_of(cfg)
+    y = torch.zeros_like(inp.x)
+    aux = torch.zeros(cfg.G, dtype=torch.float32, device=DEV)
+    small_ws = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, small_ws)
+    assert ei.value.status == -3
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_workspace_bytes(moe.MoEShape(1, 64, 30, 64, 4, 32, "f32"))   # M % 8 != 0
+    assert ei.value.status == -2
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_workspace_bytes(moe.MoEShape(1, 64, 32, 64, 1, 32, "f32"))   # E < 2
+    assert ei.value.status == -1
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_workspace_bytes(moe.MoEShape(0, 64, 32, 64, 4, 32, "f32"))   # empty batch
+    assert ei.value.status == -1
+    torch.cuda.synchronize()
+    assert (y == 0).all()
