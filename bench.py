@@ -1,0 +1,148 @@
+"""Benchmark of the MoE-layer forward pass on one MI355X.
+
+A step is one call of moe_forward (gating, dispatch, both expert GEMMs, combine)
+over one batch of seeded synthetic input that is already resident in HBM.  The
+workload is the paper-shaped layer share (G=8, S=4096, M=1024, H=8192, E=32,
+C=256, bf16 experts, fp32 gate) unless --config names another one.
+
+Prints ONE JSON line: tokens/s of the whole layer, the roofline of the dominant
+kernel (the slower of the two grouped expert GEMMs) measured with HIP events
+recorded inside the timed region on the kernels' own stream, per-stage times, and
+the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(cfg, inp, seconds_hint=20.0):
+    """The oracle as it stands, on whole groups of the same workload (groups are
+    independent, Section 2.2), as many as fit a ~10-30 s budget."""
+    import numpy as np
+    import torch
+    from oracle import moe_oracle as orc
+    from workloads import ExpertWeightsF64
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    wi, wo = ExpertWeightsF64(inp.wi), ExpertWeightsF64(inp.wo)
+    x, wg, u = inp.host_f64()
+    done, t_total = 0, 0.0
+    for g in range(cfg.G):
+        t0 = time.perf_counter()
+        orc.moe_forward(x[g:g + 1], wg, u[g:g + 1], wi, wo, cfg.C)
+        t_total += time.perf_counter() - t0
+        done += 1
+        if t_total * (done + 1) / done > seconds_hint:
+            break
+    toks = done * cfg.S
+    return {"value": toks / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{done} of {cfg.G} groups ({toks} tokens) of the same workload, whole layer, "
+                      f"fp64 numpy, {t_total:.1f} s; includes widening each expert's weights to fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="paper")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the layer on ONE GPU (one device's share of tokens); "
+                 "the cross-device exchange is out of scope, so --gpus must be 1")
+
+    import torch
+    import paper_2006_16668_amd as moe
+    from workloads import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    inp = make_inputs(cfg, device=dev)
+    sh = moe.MoEShape(cfg.G, cfg.S, cfg.M, cfg.H, cfg.E, cfg.C, cfg.act_dtype)
+    y = torch.empty_like(inp.x)
+    aux = torch.empty(cfg.G, dtype=torch.float32, device=dev)
+    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+
+    # occupied expert rows (algorithmic work of the GEMMs counts kept rows only)
+    i32 = dict(dtype=torch.int32, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    fill = torch.empty((cfg.G, cfg.E), **i32)
+    gws = torch.empty(moe.moe_gate_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_gate(sh, inp.x, inp.wg, inp.u, torch.empty((cfg.G, cfg.S, 2), **i32),
+                 torch.empty((cfg.G, cfg.S, 2), **i32), torch.empty((cfg.G, cfg.S, 2), **f32), fill,
+                 torch.empty((cfg.E, cfg.G, cfg.C), **i32), torch.empty((cfg.G, cfg.E), **i32),
+                 torch.empty((cfg.G, cfg.E), **f32), torch.empty((cfg.G,), **f32), None, gws)
+    torch.cuda.synchronize()
+    kept_rows = int(fill.sum().item())
+    padded_rows = cfg.E * cfg.G * cfg.C
+
+    K, W = args.steps, args.warmup
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
+              for _ in range(K)]
+    for evs in events:                      # create the handles
+        for e in evs:
+            e.record()
+    for _ in range(W):
+        moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        moe.moe_forward_events(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws, events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    names = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
+    stage_ms = {n: sum(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K)) / K
+                for i, n in enumerate(names)}
+    elt = 2 if cfg.act_dtype == "bf16" else 4
+    flops_launch = 2.0 * cfg.M * cfg.H * kept_rows            # per GEMM launch, kept rows only
+    dom = max(("expert_gemm1", "expert_gemm2"), key=lambda n: stage_ms[n])
+    achieved = flops_launch / (stage_ms[dom] * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg.act_dtype == "bf16" else PEAK_F32_TFLOPS
+    row_b = cfg.M * elt
+    hbm_bytes = {  # algorithmic bytes per launch of the memory-bound stages
+        "gate": cfg.N * row_b + cfg.M * cfg.E * 4 + cfg.N * 28,
+        "dispatch": (kept_rows + padded_rows) * row_b,        # read kept rows, write every slot
+        "combine": (kept_rows + cfg.N) * row_b,
+    }
+    out = {
+        "metric": "MoE-layer forward tokens/sec on 1 MI355X", "value": cfg.N * K / (t1 - t0),
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.act_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: G={cfg.G} S={cfg.S} M={cfg.M} H={cfg.H} E={cfg.E} "
+                               f"C={cfg.C}, top-2, {cfg.act_dtype} experts, fp32 gate",
+                   "tokens": cfg.N, "kept_rows": kept_rows, "padded_rows": padded_rows},
+        "roofline": {"bound": "mfma", "kernel": f"expert_gemm_bf16_kernel ({dom})",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
+        "stages_ms": stage_ms,
+        "stages_hbm_frac": {n: hbm_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS
+                            for n in hbm_bytes},
+        "ffn_mfma_frac": 2 * flops_launch / ((stage_ms["expert_gemm1"] + stage_ms["expert_gemm2"]) * 1e-3)
+                         / 1e12 / peak,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

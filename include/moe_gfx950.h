@@ -139,6 +139,20 @@ int moe_forward(const moe_config* cfg, const void* x, const float* wg, const flo
                 const void* wi, const void* wo, void* y, float* aux,
                 void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * moe_forward with stage timing marks, for callers that measure the kernels of
+ * Algorithm 2 one by one.  Identical work on the same stream; in addition the
+ * caller's MOE_FORWARD_EVENTS events (hipEvent_t handles created with timing
+ * enabled; host array of handles) are recorded on `stream`:
+ *   [0] start  [1] after gating  [2] after dispatch  [3] after h = relu(buf.wi)
+ *   [4] after out = h.wo  [5] after combine.
+ * events == NULL is exactly moe_forward.  The events stay owned by the caller.
+ */
+#define MOE_FORWARD_EVENTS 6
+int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                       const void* wi, const void* wo, void* y, float* aux,
+                       void* ws, size_t ws_bytes, void* stream, void* const* events);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ MOE_F32, MOE_BF16 = 0, 1
 SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
-           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward")
+           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events")
+FORWARD_EVENTS = 6
 
 
 class MoEError(RuntimeError):
@@ -80,6 +81,8 @@ def load_library() -> ctypes.CDLL:
         "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
         "moe_combine": [cfgp, vp, vp, vp, vp, vp, vp],
         "moe_forward": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "moe_forward_events": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
+                               ctypes.POINTER(ctypes.c_void_p)],
     }.items():
         fn = getattr(lib, name)
         fn.restype = i32
@@ -194,3 +197,21 @@ def moe_forward(shape: MoEShape, x, wg, u, wi, wo, y, aux, ws):
         _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
         _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream()),
         "moe_forward")
+
+
+def moe_forward_events(shape: MoEShape, x, wg, u, wi, wo, y, aux, ws, events):
+    """moe_forward that records ``events`` (FORWARD_EVENTS torch.cuda.Event objects, timing
+    enabled, each recorded at least once before so that its handle exists) at the stage
+    boundaries, on the stream the kernels run on."""
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    dt, f32 = shape.torch_dtype, torch.float32
+    if len(events) != FORWARD_EVENTS:
+        raise ValueError(f"need {FORWARD_EVENTS} events")
+    handles = (ctypes.c_void_p * FORWARD_EVENTS)(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_forward_events(
+        ctypes.byref(c), _ptr(x, dt, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"),
+        _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
+        _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream(), handles),
+        "moe_forward_events")

@@ -109,7 +109,10 @@ int moe_expert_ffn(const moe_config* cfg, const void* buf, const void* wi, const
   const void* req[] = {buf, wi, wo, h_ws, out};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
-  return moe::launch_expert_ffn(*cfg, buf, wi, wo, h_ws, out, static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int rc1 = moe::launch_expert_gemm1(*cfg, buf, wi, h_ws, st);
+  if (rc1 != MOE_OK) return rc1;
+  return moe::launch_expert_gemm2(*cfg, h_ws, wo, out, st);
 }
 
 int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_idx,
@@ -123,34 +126,56 @@ int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_id
                              static_cast<hipStream_t>(stream));
 }
 
-int moe_forward(const moe_config* cfg, const void* x, const float* wg, const float* u,
-                const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
-                void* stream) {
+int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                       const void* wi, const void* wo, void* y, float* aux, void* ws,
+                       size_t ws_bytes, void* stream, void* const* events) {
   int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
   const void* req[] = {x, wg, u, wi, wo, y, aux, ws};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
   if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  if (events != nullptr)
+    for (int i = 0; i < MOE_FORWARD_EVENTS; ++i)
+      if (events[i] == nullptr) return MOE_EINVAL;
   const ForwardWs w = carve(*cfg);
   if (ws_bytes < w.total) return MOE_EWORKSPACE;
   char* base = static_cast<char*>(ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  auto mark = [&](int i) {
+    return events == nullptr ||
+           hipEventRecord(static_cast<hipEvent_t>(events[i]), st) == hipSuccess;
+  };
   int32_t* expert_idx = reinterpret_cast<int32_t*>(base + w.expert_idx);
   int32_t* slot = reinterpret_cast<int32_t*>(base + w.slot);
   float* weight = reinterpret_cast<float*>(base + w.weight);
   int32_t* src_token = reinterpret_cast<int32_t*>(base + w.src_token);
+  if (!mark(0)) return MOE_EHIP;
   rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
                         reinterpret_cast<int32_t*>(base + w.fill), src_token,
                         reinterpret_cast<int32_t*>(base + w.c1),
                         reinterpret_cast<float*>(base + w.mean_gate), aux, nullptr,
                         base + w.gate_ws, st);
   if (rc != MOE_OK) return rc;
+  if (!mark(1)) return MOE_EHIP;
   rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
   if (rc != MOE_OK) return rc;
-  rc = moe::launch_expert_ffn(*cfg, base + w.buf, wi, wo, base + w.h, base + w.out, st);
+  if (!mark(2)) return MOE_EHIP;
+  rc = moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
   if (rc != MOE_OK) return rc;
-  return moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+  if (!mark(3)) return MOE_EHIP;
+  rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(4)) return MOE_EHIP;
+  rc = moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+  if (rc != MOE_OK) return rc;
+  return mark(5) ? MOE_OK : MOE_EHIP;
+}
+
+int moe_forward(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
+                void* stream) {
+  return moe_forward_events(cfg, x, wg, u, wi, wo, y, aux, ws, ws_bytes, stream, nullptr);
 }
 
 }  // extern "C"

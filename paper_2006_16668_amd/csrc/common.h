@@ -58,8 +58,11 @@ int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token
                     hipStream_t st);
 int launch_combine(const moe_config& c, const void* out, const int32_t* expert_idx,
                    const int32_t* slot, const float* weight, void* y, hipStream_t st);
-int launch_expert_ffn(const moe_config& c, const void* buf, const void* wi, const void* wo,
-                      void* h, void* out, hipStream_t st);
+// h = relu(buf . wi) and out = h . wo, one grouped GEMM launch each
+int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, void* h,
+                        hipStream_t st);
+int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,
+                        hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 

@@ -249,22 +249,33 @@ int gemm_f32(const float* A, const float* B, float* Cout, int E, int R, int N, i
 
 }  // namespace
 
-int launch_expert_ffn(const moe_config& c, const void* buf, const void* wi, const void* wo,
-                      void* h, void* out, hipStream_t st) {
+static int rows_per_expert(const moe_config& c, int* R) {
   const long long rows = (long long)c.G * c.C;
   if (rows > 0x7fffffffLL) return MOE_EUNSUPPORTED;
-  const int R = (int)rows;
-  int rc;
-  if (c.act_dtype == MOE_F32) {
-    rc = gemm_f32<true>(static_cast<const float*>(buf), static_cast<const float*>(wi),
-                        static_cast<float*>(h), c.E, R, c.H, c.M, st);
-    if (rc != MOE_OK) return rc;
+  *R = (int)rows;
+  return MOE_OK;
+}
+
+int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, void* h,
+                        hipStream_t st) {
+  int R;
+  const int rc = rows_per_expert(c, &R);
+  if (rc != MOE_OK) return rc;
+  if (c.act_dtype == MOE_F32)
+    return gemm_f32<true>(static_cast<const float*>(buf), static_cast<const float*>(wi),
+                          static_cast<float*>(h), c.E, R, c.H, c.M, st);
+  return gemm_bf16<true>(static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(wi),
+                         static_cast<bf16_t*>(h), c.E, R, c.H, c.M, st);
+}
+
+int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,
+                        hipStream_t st) {
+  int R;
+  const int rc = rows_per_expert(c, &R);
+  if (rc != MOE_OK) return rc;
+  if (c.act_dtype == MOE_F32)
     return gemm_f32<false>(static_cast<const float*>(h), static_cast<const float*>(wo),
                            static_cast<float*>(out), c.E, R, c.M, c.H, st);
-  }
-  rc = gemm_bf16<true>(static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(wi),
-                       static_cast<bf16_t*>(h), c.E, R, c.H, c.M, st);
-  if (rc != MOE_OK) return rc;
   return gemm_bf16<false>(static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo),
                           static_cast<bf16_t*>(out), c.E, R, c.M, c.H, st);
 }
