@@ -11,6 +11,14 @@
 //                       = position in the expert buffer; capacity test; combine
 //                       weights; inverse map slot -> token
 //
+// bf16 activations take the MFMA form of the first kernel (gate_mfma_*): x is
+// exactly bf16, so with wg split into three bf16 terms (hi + mid + lo = all 24
+// mantissa bits) every product is exact in fp32 and only the accumulation order
+// differs from a plain fp32 dot product.  wg is repacked once per call into the
+// lane order of the v_mfma_f32_32x32x16_bf16 B operand, so each B load is one
+// contiguous 1 KB read.  fp32 activations (and very wide gates) keep the plain
+// FMA kernel.
+//
 // Positions never come from atomics: they are exact counts of earlier tokens, so
 // the result equals the sequential two-pass loop of Algorithm 1 bit for bit.
 #include <limits.h>
@@ -139,6 +147,308 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(
   }
 }
 
+// ----------------------------------------------------------------------------
+// MFMA form for bf16 activations
+// ----------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// K order inside a block of 64 model features: MFMA step j (0..3), lane half h,
+// element i  <->  feature 32 h + 8 j + i.  A lane of the A operand then owns 64
+// contiguous bytes of its token row per block (four 16-byte loads).
+//
+// wgP[ks][t][split][lane] (uint4 = 8 bf16): B operand of step ks = 4 kb + j for
+// the 32 experts of column tile t; lane = 32 h + c holds expert 32 t + c.
+__global__ __launch_bounds__(256) void gate_pack_wg_kernel(
+    const float* __restrict__ wg, uint4* __restrict__ wgP, int M, int E, int T, int total) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = idx & 63, t = (idx >> 6) % T, ks = (idx >> 6) / T;
+  const int h = lane >> 5, col = 32 * t + (lane & 31);
+  const int m0 = (ks >> 2) * 64 + 32 * h + 8 * (ks & 3);
+  uint32_t w[3][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int m = m0 + i;
+    const float v = (m < M && col < E) ? wg[(size_t)m * E + col] : 0.f;
+    const bf16_t hi = f32_to_bf16(v);
+    const float r1 = v - bf16_to_f32(hi);          // exact
+    const bf16_t mid = f32_to_bf16(r1);
+    const float r2 = r1 - bf16_to_f32(mid);        // exact
+    const bf16_t lo = f32_to_bf16(r2);
+    const bf16_t parts[3] = {hi, mid, lo};
+#pragma unroll
+    for (int sp = 0; sp < 3; ++sp) {
+      if (i & 1) w[sp][i >> 1] |= (uint32_t)parts[sp] << 16;
+      else w[sp][i >> 1] = parts[sp];
+    }
+  }
+#pragma unroll
+  for (int sp = 0; sp < 3; ++sp)
+    wgP[((size_t)(ks * T + t) * 3 + sp) * 64 + lane] = uint4{w[sp][0], w[sp][1], w[sp][2], w[sp][3]};
+}
+
+struct Top2 { float v1; int e1; float v2; int e2; };
+
+__device__ __forceinline__ bool better(float a, int ia, float b, int ib) {
+  return a > b || (a == b && ia < ib);
+}
+__device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
+  // winner = better first entry; runner-up = better of the loser's first and the winner's second
+  const bool bw = better(b.v1, b.e1, a.v1, a.e1);
+  const float wv1 = bw ? b.v1 : a.v1, lv1 = bw ? a.v1 : b.v1, wv2 = bw ? b.v2 : a.v2;
+  const int we1 = bw ? b.e1 : a.e1, le1 = bw ? a.e1 : b.e1, we2 = bw ? b.e2 : a.e2;
+  const bool lb = better(lv1, le1, wv2, we2);
+  Top2 r;
+  r.v1 = wv1; r.e1 = we1;
+  r.v2 = lb ? lv1 : wv2; r.e2 = lb ? le1 : we2;
+  return r;
+}
+
+// Softmax / top-2 / random routing / chunk statistics for the 64 tokens of one
+// chunk whose logits sit in LDS (zs, row pitch `pitch` floats).  256 threads:
+// four per token, expert e handled by thread e % 4 of the token's quad.
+// Must be called by all threads of the block; ends with a barrier.
+__device__ __forceinline__ void gate_chunk_epilogue(
+    float* zs, int pitch, int g, int ch, int S, int E, int nch, const float* __restrict__ u,
+    int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
+    float* __restrict__ gates_opt, int32_t* __restrict__ hist1, int32_t* __restrict__ hist2,
+    float* __restrict__ msum, int* h1, int* h2) {
+  const int tid = threadIdx.x;
+  for (int e = tid; e < E; e += 256) { h1[e] = 0; h2[e] = 0; }
+  __syncthreads();
+  const int tk = tid >> 2, sub = tid & 3;
+  const int s = ch * kChunk + tk;
+  const bool valid = s < S;
+  const size_t n = (size_t)g * S + (valid ? s : 0);
+  float* zr = zs + (size_t)tk * pitch;
+  Top2 t2{-INFINITY, INT_MAX, -INFINITY, INT_MAX};
+  for (int e = sub; e < E; e += 4) {
+    const float z = zr[e];
+    if (better(z, e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z; t2.e1 = e; }
+    else if (better(z, e, t2.v2, t2.e2)) { t2.v2 = z; t2.e2 = e; }
+  }
+#pragma unroll
+  for (int o = 1; o <= 2; o <<= 1) {
+    Top2 other;
+    other.v1 = __shfl_xor(t2.v1, o, 64); other.e1 = __shfl_xor(t2.e1, o, 64);
+    other.v2 = __shfl_xor(t2.v2, o, 64); other.e2 = __shfl_xor(t2.e2, o, 64);
+    t2 = top2_merge(t2, other);
+  }
+  float psum = 0.f;
+  for (int e = sub; e < E; e += 4) {
+    const float p = expf(zr[e] - t2.v1);
+    zr[e] = p;
+    psum += p;
+  }
+  psum += __shfl_xor(psum, 1, 64);
+  psum += __shfl_xor(psum, 2, 64);
+  const float inv = 1.0f / psum;
+  for (int e = sub; e < E; e += 4) {
+    const float gate = zr[e] * inv;
+    zr[e] = gate;
+    if (gates_opt != nullptr && valid) gates_opt[n * E + e] = gate;
+  }
+  if (sub == 0 && valid) {
+    const float p2 = expf(t2.v2 - t2.v1);
+    const float g1n = 1.0f / (1.0f + p2);
+    const float g2n = p2 / (1.0f + p2);
+    const bool sampled = 2.0f * g2n > u[n];
+    expert_idx[2 * n] = t2.e1;
+    expert_idx[2 * n + 1] = t2.e2;
+    weight[2 * n] = g1n;            // provisional: zeroed later if the slot is lost
+    weight[2 * n + 1] = g2n;
+    slot[2 * n + 1] = sampled ? 0 : MOE_SLOT_NOT_SAMPLED;
+    atomicAdd(&h1[t2.e1], 1);
+    if (sampled) atomicAdd(&h2[t2.e2], 1);
+  }
+  __syncthreads();
+  const int nv = min(kChunk, S - ch * kChunk);     // valid tokens of this chunk
+  const size_t base = ((size_t)g * nch + ch) * E;
+  for (int e = tid; e < E; e += 256) {
+    float tot = 0.f;
+    for (int r = 0; r < nv; ++r) tot += zs[(size_t)r * pitch + e];
+    msum[base + e] = tot;
+    hist1[base + e] = h1[e];
+    hist2[base + e] = h2[e];
+  }
+  __syncthreads();
+}
+
+#define MOE_GATE_MFMA(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16( \
+    __builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B), C, 0, 0, 0)
+
+// Narrow gates (E <= 64): a wavefront owns 32 tokens and all experts; a block is
+// 128 tokens = two chunks.  x goes from global memory straight into the A operand.
+template <int ET>
+__global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
+    const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
+    int S, int M, int E, int nch,
+    int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
+    float* __restrict__ gates_opt,
+    int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
+  constexpr int Epad = 32 * ET, pitch = Epad + 1;
+  __shared__ float zs[128 * pitch];
+  __shared__ int hh[2 * Epad];
+  const int npair = (nch + 1) / 2;
+  const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  int s = pr * 128 + wave * 32 + r;
+  s = s < S ? s : S - 1;                              // clamp: surplus rows are ignored later
+  const bf16_t* xrow = x + ((size_t)g * S + s) * M + 32 * h;
+  const int KB = (M + 63) / 64;
+
+  f32x16_t acc[ET];
+#pragma unroll
+  for (int t = 0; t < ET; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+  uint4 a_cur[4], a_nxt[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+  {
+    a_cur[j] = uint4{0u, 0u, 0u, 0u};
+    if (32 * h + 8 * j < M) a_cur[j] = *reinterpret_cast<const uint4*>(xrow + 8 * j);
+  }
+  for (int kb = 0; kb < KB; ++kb) {
+    if (kb + 1 < KB) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int m = (kb + 1) * 64 + 32 * h + 8 * j;
+        a_nxt[j] = uint4{0u, 0u, 0u, 0u};
+        if (m < M) a_nxt[j] = *reinterpret_cast<const uint4*>(xrow + (kb + 1) * 64 + 8 * j);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4* bp = wgP + (size_t)((kb * 4 + j) * ET) * 3 * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < ET; ++t) {
+        const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
+        acc[t] = MOE_GATE_MFMA(a_cur[j], b2, acc[t]);
+        acc[t] = MOE_GATE_MFMA(a_cur[j], b1, acc[t]);
+        acc[t] = MOE_GATE_MFMA(a_cur[j], b0, acc[t]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a_cur[j] = a_nxt[j];
+  }
+  // acc[t][i]: token row 8 (i/4) + 4 h + i%4 of this wave, expert 32 t + r
+#pragma unroll
+  for (int t = 0; t < ET; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      zs[(wave * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[t][i];
+  __syncthreads();
+#pragma unroll 1
+  for (int c = 0; c < 2; ++c) {
+    const int ch = pr * 2 + c;
+    if (ch < nch)
+      gate_chunk_epilogue(zs + c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight,
+                          gates_opt, hist1, hist2, msum, hh, hh + Epad);
+  }
+}
+
+// Wide gates (64 < E <= 512): the four wavefronts of a block share 128 tokens
+// (staged through LDS) and each owns ETW column tiles of 32 experts.
+template <int ETW>
+__global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
+    const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
+    int S, int M, int E, int nch,
+    int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
+    float* __restrict__ gates_opt,
+    int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
+  constexpr int Epad = 128 * ETW, T = 4 * ETW, pitch = Epad + 1;
+  constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
+  constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
+  constexpr int kZBytes = 64 * pitch * 4;              // logits of one chunk
+  constexpr int kUnion = kABytes > kZBytes ? kABytes : kZBytes;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kUnion];
+  __shared__ int hh[2 * Epad];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);
+  float* zs = reinterpret_cast<float*>(smem);
+
+  const int npair = (nch + 1) / 2;
+  const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  const int KB = (M + 63) / 64;
+
+  // cooperative A loads: 128 rows x 64 features = 1024 16-byte vectors, 4 per thread
+  const int lrow = tid >> 3, lvec = tid & 7;           // rows lrow + 32 i
+  const bf16_t* xg = x + (size_t)g * S * M + lvec * 8;
+  uint4 areg[4];
+  auto row_of = [&](int i) { int s = pr * 128 + lrow + 32 * i; return s < S ? s : S - 1; };
+#define MOE_GATE_LOAD_A(kb)                                                              \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
+    const int m = (kb) * 64 + lvec * 8;                                                  \
+    areg[i] = uint4{0u, 0u, 0u, 0u};                                                     \
+    if (m < M) areg[i] = *reinterpret_cast<const uint4*>(xg + (size_t)row_of(i) * M + (kb) * 64); \
+  }
+#define MOE_GATE_STORE_A(buf)                                                            \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
+    *reinterpret_cast<uint4*>(As + (buf) * 128 * kAPitch + (lrow + 32 * i) * kAPitch + lvec * 8) = areg[i];
+
+  f32x16_t acc[4][ETW];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int t = 0; t < ETW; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
+
+  MOE_GATE_LOAD_A(0)
+  MOE_GATE_STORE_A(0)
+  __syncthreads();
+  for (int kb = 0; kb < KB; ++kb) {
+    const int cur = kb & 1;
+    if (kb + 1 < KB) { MOE_GATE_LOAD_A(kb + 1) }
+    const bf16_t* as = As + cur * 128 * kAPitch + r * kAPitch + 32 * h;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint4 af[4];
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt)
+        af[rt] = *reinterpret_cast<const uint4*>(as + rt * 32 * kAPitch + 8 * j);
+      const uint4* bp = wgP + ((size_t)(kb * 4 + j) * T + wave * ETW) * 3 * 64 + lane;
+#pragma unroll
+      for (int t = 0; t < ETW; ++t) {
+        const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], b2, acc[rt][t]);
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], b1, acc[rt][t]);
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], b0, acc[rt][t]);
+        }
+      }
+    }
+    if (kb + 1 < KB) { MOE_GATE_STORE_A(cur ^ 1) }
+    __syncthreads();
+  }
+#undef MOE_GATE_LOAD_A
+#undef MOE_GATE_STORE_A
+  // the A stages are dead from here on; the same LDS holds one chunk of logits at a time
+#pragma unroll 1
+  for (int c = 0; c < 2; ++c) {
+    const int ch = pr * 2 + c;
+    if (ch >= nch) break;                              // block-uniform
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+      for (int t = 0; t < ETW; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
+              c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
+    __syncthreads();
+    gate_chunk_epilogue(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt, hist1,
+                        hist2, msum, hh, hh + Epad);
+  }
+}
+#undef MOE_GATE_MFMA
+
 // One block per group.  hist1/hist2 are replaced by their exclusive prefix over
 // chunks; hist2's prefix starts at c1 (second choices queue behind all first ones).
 __global__ __launch_bounds__(256) void gate_scan_kernel(
@@ -246,9 +556,21 @@ int launch_topk(const moe_config& c, int nch, const T* x, const float* wg, const
 
 }  // namespace
 
+// Geometry of the packed gate weights (bf16 MFMA path).
+struct PackGeom { int T, KS; size_t bytes; };
+static PackGeom pack_geom(const moe_config& c) {
+  PackGeom p{};
+  if (c.act_dtype != MOE_BF16 || c.E > 512) return p;   // bytes == 0: plain kernel
+  const int epad = c.E <= 64 ? (c.E + 31) / 32 * 32 : (c.E + 127) / 128 * 128;
+  p.T = epad / 32;
+  p.KS = (c.M + 63) / 64 * 4;
+  p.bytes = (size_t)p.KS * p.T * 3 * 64 * 16;
+  return p;
+}
+
 size_t gate_workspace_bytes(const moe_config& c) {
   const size_t nch = (size_t)(c.S + kChunk - 1) / kChunk;
-  return 3 * align_up((size_t)c.G * nch * c.E * 4, 256);
+  return 3 * align_up((size_t)c.G * nch * c.E * 4, 256) + align_up(pack_geom(c).bytes, 256);
 }
 
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
@@ -260,13 +582,32 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
   int32_t* hist1 = reinterpret_cast<int32_t*>(ws);
   int32_t* hist2 = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + seg);
   float* msum = reinterpret_cast<float*>(static_cast<char*>(ws) + 2 * seg);
+  uint4* wgP = reinterpret_cast<uint4*>(static_cast<char*>(ws) + 3 * seg);
+  const PackGeom pg = pack_geom(c);
   int rc;
-  if (c.act_dtype == MOE_F32)
+  if (c.act_dtype == MOE_F32) {
     rc = launch_topk<float>(c, nch, static_cast<const float*>(x), wg, u, expert_idx, slot, weight,
                             gates_opt, hist1, hist2, msum, st);
-  else
+  } else if (pg.bytes == 0) {
     rc = launch_topk<bf16_t>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
                              weight, gates_opt, hist1, hist2, msum, st);
+  } else {
+    const int total = pg.KS * pg.T * 64;
+    hipLaunchKernelGGL(gate_pack_wg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       wg, wgP, c.M, c.E, pg.T, total);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), block(256);
+    const bf16_t* xb = static_cast<const bf16_t*>(x);
+#define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
+    if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) hipLaunchKernelGGL(gate_mfma_cols_kernel<1>, grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 256) hipLaunchKernelGGL(gate_mfma_cols_kernel<2>, grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 384) hipLaunchKernelGGL(gate_mfma_cols_kernel<3>, grid, block, 0, st, MOE_GATE_ARGS);
+    else hipLaunchKernelGGL(gate_mfma_cols_kernel<4>, grid, block, 0, st, MOE_GATE_ARGS);
+#undef MOE_GATE_ARGS
+    rc = check_launch();
+  }
   if (rc != MOE_OK) return rc;
   hipLaunchKernelGGL(gate_scan_kernel, dim3((unsigned)c.G), dim3(256), 0, st, c.S, c.E, c.C, c.G,
                      nch, hist1, hist2, msum, c1, mean_gate, fill, src_token, aux);

@@ -32,6 +32,13 @@ SMALL_CASES = [
     MoEConfig("capacity_one", G=4, S=70, M=32, H=32, E=6, C=1, act_dtype="bf16", seed=15),
     MoEConfig("one_token", G=5, S=1, M=16, H=24, E=3, C=2, act_dtype="f32", seed=16),
     MoEConfig("wide_rows", G=2, S=520, M=256, H=520, E=3, C=300, act_dtype="bf16", seed=17),
+    # one case per width class of the gate kernels (<=32, <=64, <=128, <=256, <=384, <=512, wider)
+    MoEConfig("e48", G=2, S=190, M=96, H=32, E=48, C=9, act_dtype="bf16", seed=18),
+    MoEConfig("e100", G=3, S=129, M=200, H=32, E=100, C=4, act_dtype="bf16", seed=19),
+    MoEConfig("e300", G=1, S=333, M=72, H=32, E=300, C=3, act_dtype="bf16", seed=20),
+    MoEConfig("e512", G=2, S=260, M=128, H=32, E=512, C=2, act_dtype="bf16", seed=23),
+    MoEConfig("e600", G=1, S=100, M=64, H=32, E=600, C=1, act_dtype="bf16", seed=24),
+    MoEConfig("e130_f32", G=1, S=150, M=48, H=32, E=130, C=3, act_dtype="f32", seed=25),
 ]
 
 
