@@ -17,7 +17,7 @@ SOURCES = ["api.hip", "gate.hip", "dispatch_combine.hip", "expert_gemm.hip"]
 # packed-fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Wno-dangling-else"]
 
 
 def _hipcc() -> str:

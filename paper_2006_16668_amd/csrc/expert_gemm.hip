@@ -22,6 +22,7 @@ namespace {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector
 
 constexpr int kXcds = 8;
 
@@ -40,7 +41,7 @@ struct GemmSmem {
   static constexpr size_t kBytes = (size_t)2 * (kAElems + kBElems) * sizeof(bf16_t);
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU>
+template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
     int R, int N, int K, int tiles_m, int tiles_n, int nblk) {
@@ -68,34 +69,54 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
   const bf16_t* Be = B + (size_t)e * K * N;
   bf16_t* Ce = Cout + (size_t)e * R * N;
 
-  uint4 areg[AV], breg[BV];
+  u32x4_t areg[1][AV], breg[1][BV];   // staging registers of the tile in flight
   bf16_t* const as_w = As + (tid / (BK / 8)) * SM::kAPitch + (tid % (BK / 8)) * 8;
   bf16_t* const bs_w = Bs + (tid / (BN / 8)) * SM::kBPitch + (tid % (BN / 8)) * 8;
 
-#define MOE_LOAD_TILES(k0)                                                                   \
-  {                                                                                          \
+  // Loads are branch-free.  EXACT tiles: uniform (scalar) base + one per-lane byte
+  // offset, so the loads of a tile share a single address register.  Ragged tiles:
+  // addresses are clamped into the matrix and lanes that fall outside K or N are
+  // zeroed by a select afterwards.
+  const uint32_t a_lane = (uint32_t)(((tid / (BK / 8)) * K + (tid % (BK / 8)) * 8) * 2);
+  const uint32_t b_lane = (uint32_t)(((tid / (BN / 8)) * N + (tid % (BN / 8)) * 8) * 2);
+  const char* const a_tile = reinterpret_cast<const char*>(Ae + (size_t)m0 * K);
+  const char* const b_tile = reinterpret_cast<const char*>(Be + n0);
+#define MOE_LOAD_TILES(S, k0)                                                                \
+  if (EXACT) {                                                                               \
+    _Pragma("unroll") for (int i = 0; i < AV; ++i)                                           \
+      areg[S][i] = *reinterpret_cast<const u32x4_t*>(                                          \
+          a_tile + ((size_t)(i * (256 / (BK / 8))) * K + (k0)) * 2 + a_lane);                \
+    _Pragma("unroll") for (int i = 0; i < BV; ++i)                                           \
+      breg[S][i] = *reinterpret_cast<const u32x4_t*>(                                          \
+          b_tile + ((size_t)((k0) + i * (256 / (BN / 8))) * N) * 2 + b_lane);                \
+  } else {                                                                                   \
     _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                         \
       int gr = m0 + i * (256 / (BK / 8)) + tid / (BK / 8);                                   \
-      gr = gr < R ? gr : R - 1; /* clamp: extra rows are never stored */                     \
-      const int gk = (k0) + (tid % (BK / 8)) * 8;                                            \
-      areg[i] = gk < K ? *reinterpret_cast<const uint4*>(Ae + (size_t)gr * K + gk)           \
-                       : uint4{0u, 0u, 0u, 0u};                                              \
+      int gk = (k0) + (tid % (BK / 8)) * 8;                                                  \
+      gr = gr < R ? gr : R - 1; /* surplus rows are never stored */                          \
+      const bool ok = gk < K;                                                                \
+      gk = ok ? gk : K - 8;                                                                  \
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(Ae + (size_t)gr * K + gk);             \
+      areg[S][i] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};                                           \
     }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < BV; ++i) {                                         \
-      const int gk = (k0) + i * (256 / (BN / 8)) + tid / (BN / 8);                           \
-      const int gn = n0 + (tid % (BN / 8)) * 8;                                              \
-      breg[i] = (gk < K && gn < N) ? *reinterpret_cast<const uint4*>(Be + (size_t)gk * N + gn) \
-                                   : uint4{0u, 0u, 0u, 0u};                                  \
+      int gk = (k0) + i * (256 / (BN / 8)) + tid / (BN / 8);                                 \
+      int gn = n0 + (tid % (BN / 8)) * 8;                                                    \
+      const bool ok = gk < K && gn < N;                                                      \
+      gk = gk < K ? gk : K - 1;                                                              \
+      gn = gn < N ? gn : N - 8;                                                              \
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(Be + (size_t)gk * N + gn);             \
+      breg[S][i] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};                                           \
     }                                                                                        \
   }
-#define MOE_STORE_TILES(buf)                                                                 \
+#define MOE_STORE_TILES(S, buf)                                                                 \
   {                                                                                          \
     _Pragma("unroll") for (int i = 0; i < AV; ++i)                                           \
-      *reinterpret_cast<uint4*>(as_w + (buf) * SM::kAElems +                                 \
-                                i * (256 / (BK / 8)) * SM::kAPitch) = areg[i];               \
+      *reinterpret_cast<u32x4_t*>(as_w + (buf) * SM::kAElems +                                 \
+                                i * (256 / (BK / 8)) * SM::kAPitch) = areg[S][i];            \
     _Pragma("unroll") for (int i = 0; i < BV; ++i)                                           \
-      *reinterpret_cast<uint4*>(bs_w + (buf) * SM::kBElems +                                 \
-                                i * (256 / (BN / 8)) * SM::kBPitch) = breg[i];               \
+      *reinterpret_cast<u32x4_t*>(bs_w + (buf) * SM::kBElems +                                 \
+                                i * (256 / (BN / 8)) * SM::kBPitch) = breg[S][i];            \
   }
 
   f32x16_t acc[TM][TN];
@@ -110,65 +131,273 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
   const int a_off = (wm0 + (lane & 31)) * SM::kAPitch + 8 * (lane >> 5);
   const int b_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * SM::kBPitch + wn0 +
                     16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+
+  // MFMA operands of one 16-wide k step: A rows of the wave tile, B columns
+  // (each lane: 8 consecutive k of one row / column)
+  struct Frags { bf16x8_t a[TM]; bf16x8_t b[TN]; };
+#define MOE_READ_FRAGS(F, buf, kk)                                                           \
+  {                                                                                          \
+    const bf16_t* as_ = As + (buf) * SM::kAElems + a_off + (kk) * 16;                        \
+    const bf16_t* bs_ = Bs + (buf) * SM::kBElems + b_off + (kk) * 16 * SM::kBPitch;          \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+      (F).a[i] = *reinterpret_cast<const bf16x8_t*>(as_ + i * 32 * SM::kAPitch);             \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bs_ + j * 32)); \
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                            \
+          (lds_s16x4_ptr)(bs_ + j * 32 + 4 * SM::kBPitch));                                  \
+      (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                \
+                                    __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
+    }                                                                                        \
+  }
+  // The weight fragment goes in as the first MFMA operand: the 32x32 result is then
+  // the transposed tile, i.e. a lane owns 4 consecutive columns of one row of C.
+#define MOE_MFMA_STEP(F)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                             \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((F).b[j], (F).a[i], acc[i][j], 0, 0, 0);
 
   const int KT = (K + BK - 1) / BK;
-  MOE_LOAD_TILES(0)
-  MOE_STORE_TILES(0)
+  constexpr int KK = BK / 16;
+  Frags fr[2];
+  // Pipeline: tile kt is consumed from LDS stage kt&1 while tile kt+1 travels
+  // through the staging registers (loaded right after the barrier, written to the
+  // other LDS stage during the last k step).
+  MOE_LOAD_TILES(0, 0)
+  MOE_STORE_TILES(0, 0)
   __syncthreads();
-
+  if (KT > 1) MOE_LOAD_TILES(0, BK)
+  MOE_READ_FRAGS(fr[0], 0, 0)
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < KT) MOE_LOAD_TILES((kt + 1) * BK)
-    const bf16_t* as = As + cur * SM::kAElems + a_off;
-    const bf16_t* bs = Bs + cur * SM::kBElems + b_off;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * SM::kAPitch + kk * 16);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
-        const bf16_t* p = bs + kk * 16 * SM::kBPitch + j * 32;
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * SM::kBPitch));
-        bfr[j] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) MOE_READ_FRAGS(fr[(kk + 1) & 1], cur, kk + 1)
+      if (kk + 1 == KK && kt + 1 < KT) MOE_STORE_TILES(0, cur ^ 1)
+      MOE_MFMA_STEP(fr[kk & 1])
     }
-    if (kt + 1 < KT) MOE_STORE_TILES(cur ^ 1)
     __syncthreads();
+    if (kt + 2 < KT) MOE_LOAD_TILES(0, (kt + 2) * BK)
+    if (kt + 1 < KT) MOE_READ_FRAGS(fr[0], cur ^ 1, 0)
   }
 
-  // epilogue: acc[i][j][r] is C[row][col] with
-  //   row = 32 i + 8 (r/4) + 4 (lane/32) + r%4,  col = 32 j + lane%32
+  // epilogue: acc[i][j][r] = C[row][col .. col+3 for r%4 = 0..3] with
+  //   row = 32 i + lane%32,  col = 32 j + 8 (r/4) + 4 (lane/32)
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm0 + 32 * i + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn0 + 32 * j + (lane & 31);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        float v = acc[i][j][r];
-        if (RELU) v = fmaxf(v, 0.f);
-        if (row < R && col < N) Ce[(size_t)row * N + col] = f32_to_bf16(v);
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn0 + 32 * j + 8 * q + 4 * (lane >> 5);
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[r] = acc[i][j][4 * q + r];
+          if (RELU) v[r] = fmaxf(v[r], 0.f);
+        }
+        if (EXACT || (row < R && col < N))      // N % 8 == 0: the 4 columns are in or out together
+          *reinterpret_cast<uint2*>(Ce + (size_t)row * N + col) =
+              uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
       }
-    }
+  }
+#undef MOE_READ_FRAGS
+#undef MOE_MFMA_STEP
 #undef MOE_LOAD_TILES
 #undef MOE_STORE_TILES
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU>
-int launch_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
-                hipStream_t st) {
+// ----------------------------------------------------------------------------
+// Exact 256x256 tiles: global -> LDS copies that bypass the registers
+// (global_load_lds_dwordx4), ST stages of 32 k each, so that a load has ST-2 full
+// K steps to land.  One wavefront instruction fills 1 KB of LDS (lane l -> bytes
+// 16 l ..), which fixes the LDS layout to unpadded rows; bank conflicts are
+// avoided by permuting which 16-byte chunk of a row a lane fetches:
+//   A stage [256 rows][4 chunks of 8 k]:  chunk c of row r sits at position c ^ ((r>>1)&3)
+//   B stage [32 k][32 chunks of 8 n]:     chunk c of row k sits at position c ^ (2 (k&3))
+// Iteration kt: wait for the own loads of tile kt+1, barrier (tile kt+1 is now
+// visible to all, the stage of tile kt-1 is free), start tile kt+ST-1 into that
+// stage, multiply tile kt while fetching the first fragments of tile kt+1.
+// ----------------------------------------------------------------------------
+template <int ST>
+struct DmaSmem {
+  static constexpr int kAStage = 256 * 32 * 2, kBStage = 32 * 256 * 2;
+  static constexpr int kStage = kAStage + kBStage;
+  static constexpr size_t kBytes = (size_t)ST * kStage;
+};
+
+#define MOE_DMA16(LDS_U32, VOFF_U32, SBASE)                                         \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"     \
+               :: "s"(LDS_U32), "v"(VOFF_U32), "s"(SBASE) : "memory")
+
+template <int ST, bool RELU>
+__global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
+    int R, int N, int K, int tiles_m, int tiles_n, int nblk) {
+  using SM = DmaSmem<ST>;
+  constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  typedef unsigned char __attribute__((address_space(3))) * lds_ptr;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_ptr)smem_raw);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int logical = xcd_remap(blockIdx.x, nblk);
+  const int per_e = tiles_m * tiles_n;
+  const int e = logical / per_e;
+  const int t = logical - e * per_e;
+  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+
+  const bf16_t* a_src = A + ((size_t)e * R + m0) * K;          // + k0 per tile
+  const bf16_t* b_src = B + (size_t)e * K * N + n0;            // + k0 * N per tile
+  bf16_t* Ce = Cout + (size_t)e * R * N;
+
+  // per-lane source byte offsets of the 4 + 4 copy instructions of this wavefront
+  uint32_t a_voff[4], b_voff[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = 16 * (wave * 4 + q) + (lane >> 2);
+    const int ca = (lane & 3) ^ ((row >> 1) & 3);
+    a_voff[q] = (uint32_t)((row * K + 8 * ca) * 2);
+    const int krow = 2 * (wave * 4 + q) + (lane >> 5);
+    const int cb = (lane & 31) ^ (2 * (krow & 3));
+    b_voff[q] = (uint32_t)((krow * N + 8 * cb) * 2);
+  }
+#define MOE_DMA_ISSUE(TILE, STAGE)                                                           \
+  {                                                                                          \
+    const bf16_t* as_ = a_src + (size_t)(TILE) * BK;                                         \
+    const bf16_t* bs_ = b_src + (size_t)(TILE) * BK * N;                                     \
+    const uint32_t la_ = lds0 + (STAGE) * SM::kStage + wave * 4096;                          \
+    const uint32_t lb_ = la_ + SM::kAStage;                                                  \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) MOE_DMA16(la_ + q * 1024, a_voff[q], as_); \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) MOE_DMA16(lb_ + q * 1024, b_voff[q], bs_); \
+  }
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment read offsets (bytes inside a stage)
+  //   A: row wm0 + 32 i + lane%32, chunk 2 kk + lane/32 at its permuted position
+  const int ar = lane & 31;
+  uint32_t a_rd[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk)
+    a_rd[kk] = (uint32_t)((wm0 + ar) * 64 + (((2 * kk + (lane >> 5)) ^ ((ar >> 1) & 3)) * 16));
+  //   B (transposing read): 16-lane block b = lane/16 covers k rows 8 (b/2) + (lane%16)/4 (+4),
+  //   columns wn0 + 32 j + 16 (b%2) + 4 (lane%4) .. +3; chunk = column / 8
+  const int p16 = lane & 15, bb = lane >> 4;
+  const int bk = 8 * (bb >> 1) + (p16 >> 2);                   // k row inside a 16-wide step
+  const int bsw = 2 * (bk & 3);                                // permutation of that row
+  uint32_t b_rd[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int c = (wn0 >> 3) + 4 * j + 2 * (bb & 1) + ((p16 & 3) >> 1);
+    b_rd[j] = (uint32_t)(SM::kAStage + bk * 512 + ((c ^ bsw) * 16) + (p16 & 1) * 8);
+  }
+  typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+  typedef bf16x8_t __attribute__((address_space(3))) * lds_bf16x8_ptr;
+  struct Frags { bf16x8_t a[TM]; bf16x8_t b[TN]; };
+#define MOE_DMA_READ_FRAGS(F, STAGE, kk)                                                     \
+  {                                                                                          \
+    const uint32_t sb_ = lds0 + (STAGE) * SM::kStage;                                        \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+      (F).a[i] = *(lds_bf16x8_ptr)(uintptr_t)(sb_ + a_rd[kk] + i * 32 * 64);                 \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
+      const uint32_t pb_ = sb_ + b_rd[j] + (kk) * 16 * 512;                                  \
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pb_); \
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                            \
+          (lds_s16x4_ptr)(uintptr_t)(pb_ + 4 * 512));                                        \
+      (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                \
+                                    __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
+    }                                                                                        \
+  }
+#define MOE_DMA_MFMA(F)                                                                      \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                             \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((F).b[j], (F).a[i], acc[i][j], 0, 0, 0);
+
+  const int KT = K / BK;
+  Frags fr[2];
+  for (int tl = 0; tl < ST - 1 && tl < KT; ++tl) MOE_DMA_ISSUE(tl, tl)
+  int stage = 0;                                               // stage of tile kt
+  for (int kt = 0; kt < KT; ++kt) {
+    // own copies of tile min(kt+1, KT-1) must have landed; younger tiles may still fly
+    const int issued = kt + ST - 1 < KT ? kt + ST - 1 : KT;
+    const int need = kt + 1 < KT ? kt + 1 : KT - 1;
+    const int younger = issued - 1 - need;                     // 0 .. ST-3 tiles of 8 copies
+    if (younger >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const int nstage = stage + 1 == ST ? 0 : stage + 1;        // stage of tile kt+1
+    if (kt + ST - 1 < KT) {
+      const int fstage = stage == 0 ? ST - 1 : stage - 1;      // stage of tile kt-1, now free
+      MOE_DMA_ISSUE(kt + ST - 1, fstage)
+    }
+    if (kt == 0) MOE_DMA_READ_FRAGS(fr[0], 0, 0)
+    MOE_DMA_READ_FRAGS(fr[1], stage, 1)
+    MOE_DMA_MFMA(fr[0])
+    if (kt + 1 < KT) MOE_DMA_READ_FRAGS(fr[0], nstage, 0)
+    MOE_DMA_MFMA(fr[1])
+    stage = nstage;
+  }
+
+  // epilogue: acc[i][j][4 q + r] = C[32 i + lane%32][32 j + 8 q + 4 (lane/32) + r]
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm0 + 32 * i + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn0 + 32 * j + 8 * q + 4 * (lane >> 5);
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[r] = acc[i][j][4 * q + r];
+          if (RELU) v[r] = fmaxf(v[r], 0.f);
+        }
+        *reinterpret_cast<uint2*>(Ce + (size_t)row * N + col) =
+            uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+      }
+  }
+#undef MOE_DMA_ISSUE
+#undef MOE_DMA_READ_FRAGS
+#undef MOE_DMA_MFMA
+}
+
+template <int ST, bool RELU>
+int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
+                    hipStream_t st) {
+  using SM = DmaSmem<ST>;
+  auto kern = expert_gemm_bf16_dma_kernel<ST, RELU>;
+  static bool attr_set = false;   // idempotent: a repeated call sets the same value
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytes) != hipSuccess)
+      return MOE_EHIP;
+    attr_set = true;
+  }
+  const int tiles_m = R / 256, tiles_n = N / 256;
+  const long long nblk = (long long)E * tiles_m * tiles_n;
+  if (nblk > 0x7fffffffLL) return MOE_EUNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), SM::kBytes, st, A, B, Cout, R, N, K,
+                     tiles_m, tiles_n, (int)nblk);
+  return check_launch();
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
+int launch_bf16_kernel(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
+                       hipStream_t st) {
   using SM = GemmSmem<BM, BN, BK>;
-  auto kern = expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU>;
+  auto kern = expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>;
   static bool attr_set = false;   // idempotent: a repeated call sets the same value
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -184,9 +413,21 @@ int launch_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, in
   return check_launch();
 }
 
+template <int BM, int BN, int BK, int WM, int WN, bool RELU>
+int launch_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
+                hipStream_t st) {
+  if (R % BM == 0 && N % BN == 0 && K % BK == 0)
+    return launch_bf16_kernel<BM, BN, BK, WM, WN, RELU, true>(A, B, Cout, E, R, N, K, st);
+  return launch_bf16_kernel<BM, BN, BK, WM, WN, RELU, false>(A, B, Cout, E, R, N, K, st);
+}
+
 template <bool RELU>
 int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
               hipStream_t st) {
+  // per-lane byte offsets of the register-bypassing kernel are 32-bit
+  if (R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && (long long)256 * K * 2 < (1LL << 31) &&
+      (long long)32 * N * 2 < (1LL << 31))
+    return launch_bf16_dma<4, RELU>(A, B, Cout, E, R, N, K, st);
   if (R > 128 && N >= 256) return launch_bf16<256, 256, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
   return launch_bf16<128, 128, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
 }
