@@ -129,7 +129,7 @@ def main():
         "config": {"workload": f"{cfg.name}: G={cfg.G} S={cfg.S} M={cfg.M} H={cfg.H} E={cfg.E} "
                                f"C={cfg.C}, top-2, {cfg.act_dtype} experts, fp32 gate",
                    "tokens": cfg.N, "kept_rows": kept_rows, "padded_rows": padded_rows},
-        "roofline": {"bound": "mfma", "kernel": f"expert_gemm_bf16_kernel ({dom})",
+        "roofline": {"bound": "mfma", "kernel": f"expert_gemm_bf16_dma_kernel ({dom})",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": None,
                      "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
