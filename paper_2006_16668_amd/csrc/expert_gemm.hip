@@ -214,8 +214,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
 // K steps to land.  One wavefront instruction fills 1 KB of LDS (lane l -> bytes
 // 16 l ..), which fixes the LDS layout to unpadded rows; bank conflicts are
 // avoided by permuting which 16-byte chunk of a row a lane fetches:
-//   A stage [256 rows][4 chunks of 8 k]:  chunk c of row r sits at position c ^ ((r>>1)&3)
-//   B stage [32 k][32 chunks of 8 n]:     chunk c of row k sits at position c ^ (2 (k&3))
+//   A stage [256 rows][4 chunks of 8 k]:  chunk c of row r sits at position c ^ ((r>>2)&3)
+//   B stage [32 k][32 chunks of 8 n]:     chunk c of row k sits at position c ^ (4 (k&3))
+// (64 banks of 4 bytes: a 16-lane group of a 16-byte read, or a 32-lane group of an
+// 8-byte transposing read, then touches every bank exactly once)
 // Iteration kt: wait for the own loads of tile kt+1, barrier (tile kt+1 is now
 // visible to all, the stage of tile kt-1 is free), start tile kt+ST-1 into that
 // stage, multiply tile kt while fetching the first fragments of tile kt+1.
@@ -259,10 +261,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int row = 16 * (wave * 4 + q) + (lane >> 2);
-    const int ca = (lane & 3) ^ ((row >> 1) & 3);
+    const int ca = (lane & 3) ^ ((row >> 2) & 3);
     a_voff[q] = (uint32_t)((row * K + 8 * ca) * 2);
     const int krow = 2 * (wave * 4 + q) + (lane >> 5);
-    const int cb = (lane & 31) ^ (2 * (krow & 3));
+    const int cb = (lane & 31) ^ (4 * (krow & 3));
     b_voff[q] = (uint32_t)((krow * N + 8 * cb) * 2);
   }
 #define MOE_DMA_ISSUE(TILE, STAGE)                                                           \
@@ -289,12 +291,12 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   uint32_t a_rd[2];
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk)
-    a_rd[kk] = (uint32_t)((wm0 + ar) * 64 + (((2 * kk + (lane >> 5)) ^ ((ar >> 1) & 3)) * 16));
+    a_rd[kk] = (uint32_t)((wm0 + ar) * 64 + (((2 * kk + (lane >> 5)) ^ ((ar >> 2) & 3)) * 16));
   //   B (transposing read): 16-lane block b = lane/16 covers k rows 8 (b/2) + (lane%16)/4 (+4),
   //   columns wn0 + 32 j + 16 (b%2) + 4 (lane%4) .. +3; chunk = column / 8
   const int p16 = lane & 15, bb = lane >> 4;
   const int bk = 8 * (bb >> 1) + (p16 >> 2);                   // k row inside a 16-wide step
-  const int bsw = 2 * (bk & 3);                                // permutation of that row
+  const int bsw = 4 * (bk & 3);                                // permutation of that row
   uint32_t b_rd[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -325,29 +327,40 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 
   const int KT = K / BK;
   Frags fr[2];
-  for (int tl = 0; tl < ST - 1 && tl < KT; ++tl) MOE_DMA_ISSUE(tl, tl)
+  // wait until at most `younger` tiles (8 copies each) of this wavefront are still in flight
+#define MOE_DMA_WAIT(younger)                                                                \
+  {                                                                                          \
+    if ((younger) >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                    \
+    else if ((younger) == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                    \
+  }
+  const int pro = ST - 1 < KT ? ST - 1 : KT;                   // tiles started up front
+  for (int tl = 0; tl < pro; ++tl) MOE_DMA_ISSUE(tl, tl)
+  MOE_DMA_WAIT(pro - 1)                                        // tile 0 has landed
+  __syncthreads();
+  MOE_DMA_READ_FRAGS(fr[0], 0, 0)
   int stage = 0;                                               // stage of tile kt
+  // The fragment reads are unconditional (the last iteration fetches fragments nobody
+  // multiplies, from a valid stage): a conditional read would make every later wait
+  // for LDS data wait for all outstanding reads instead of the older ones only.
   for (int kt = 0; kt < KT; ++kt) {
-    // own copies of tile min(kt+1, KT-1) must have landed; younger tiles may still fly
+    MOE_DMA_READ_FRAGS(fr[1], stage, 1)
+    MOE_DMA_MFMA(fr[0])
+    // tile kt+1 must be visible to everyone before its fragments are fetched
     const int issued = kt + ST - 1 < KT ? kt + ST - 1 : KT;
     const int need = kt + 1 < KT ? kt + 1 : KT - 1;
-    const int younger = issued - 1 - need;                     // 0 .. ST-3 tiles of 8 copies
-    if (younger >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    MOE_DMA_WAIT(issued - 1 - need)
     __syncthreads();
     const int nstage = stage + 1 == ST ? 0 : stage + 1;        // stage of tile kt+1
     if (kt + ST - 1 < KT) {
       const int fstage = stage == 0 ? ST - 1 : stage - 1;      // stage of tile kt-1, now free
       MOE_DMA_ISSUE(kt + ST - 1, fstage)
     }
-    if (kt == 0) MOE_DMA_READ_FRAGS(fr[0], 0, 0)
-    MOE_DMA_READ_FRAGS(fr[1], stage, 1)
-    MOE_DMA_MFMA(fr[0])
-    if (kt + 1 < KT) MOE_DMA_READ_FRAGS(fr[0], nstage, 0)
+    MOE_DMA_READ_FRAGS(fr[0], nstage, 0)
     MOE_DMA_MFMA(fr[1])
     stage = nstage;
   }
+#undef MOE_DMA_WAIT
 
   // epilogue: acc[i][j][4 q + r] = C[32 i + lane%32][32 j + 8 q + 4 (lane/32) + r]
 #pragma unroll
