@@ -21,8 +21,18 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+// two fp32 -> packed bf16 with the hardware conversion (v_cvt_pk_bf16_f32, round to nearest even)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// max(v, 0) on two packed bf16 in one op: a negative bf16 is a negative 16-bit integer
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t v) {
+  typedef short s16x2_t __attribute__((ext_vector_type(2)));
+  const s16x2_t zero = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, v), zero));
 }
 
 template <typename T> struct Elt;

@@ -23,6 +23,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kXcds = 8;
 
@@ -209,18 +210,27 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
 }
 
 // ----------------------------------------------------------------------------
-// Exact 256x256 tiles: global -> LDS copies that bypass the registers
-// (global_load_lds_dwordx4), ST stages of 32 k each, so that a load has ST-2 full
-// K steps to land.  One wavefront instruction fills 1 KB of LDS (lane l -> bytes
-// 16 l ..), which fixes the LDS layout to unpadded rows; bank conflicts are
-// avoided by permuting which 16-byte chunk of a row a lane fetches:
+// Exact 256x256 tiles: a persistent kernel (one block per CU) that walks its share
+// of the tiles as ONE stream of 32-wide K steps.
+//
+// Global -> LDS copies bypass the registers (global_load_lds_dwordx4), ST stages of
+// 32 KB, the copy of step g+ST-1 is started during step g, also across a tile
+// boundary: the next tile's first stages land while the current tile is finished
+// and stored, so neither the fill of the pipeline nor the drain of the stores is
+// paid per tile.
+//
+// One wavefront copy instruction fills 1 KB of LDS (lane l -> bytes 16 l ..), which
+// fixes the LDS layout to unpadded rows; bank conflicts are avoided by permuting
+// which 16-byte chunk of a row a lane fetches:
 //   A stage [256 rows][4 chunks of 8 k]:  chunk c of row r sits at position c ^ ((r>>2)&3)
 //   B stage [32 k][32 chunks of 8 n]:     chunk c of row k sits at position c ^ (4 (k&3))
 // (64 banks of 4 bytes: a 16-lane group of a 16-byte read, or a 32-lane group of an
 // 8-byte transposing read, then touches every bank exactly once)
-// Iteration kt: wait for the own loads of tile kt+1, barrier (tile kt+1 is now
-// visible to all, the stage of tile kt-1 is free), start tile kt+ST-1 into that
-// stage, multiply tile kt while fetching the first fragments of tile kt+1.
+//
+// Step g: fetch the fragments of the second k half, multiply the first half; wait
+// for the own copies of step g+1 and barrier (step g+1 is now visible to all, the
+// stage of step g-1 is free); then, spread between the four MFMA rows of the second
+// half, start the copies of step g+ST-1 and fetch the first fragments of step g+1.
 // ----------------------------------------------------------------------------
 template <int ST>
 struct DmaSmem {
@@ -236,7 +246,7 @@ struct DmaSmem {
 template <int ST, bool RELU>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
-    int R, int N, int K, int tiles_m, int tiles_n, int nblk) {
+    int R, int N, int K, int tiles_m, int tiles_n, int ntiles) {
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -245,16 +255,23 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int logical = xcd_remap(blockIdx.x, nblk);
-  const int per_e = tiles_m * tiles_n;
-  const int e = logical / per_e;
-  const int t = logical - e * per_e;
-  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
   const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+  const int per_e = tiles_m * tiles_n;
+  const int KT = K / BK;
 
-  const bf16_t* a_src = A + ((size_t)e * R + m0) * K;          // + k0 per tile
-  const bf16_t* b_src = B + (size_t)e * K * N + n0;            // + k0 * N per tile
-  bf16_t* Ce = Cout + (size_t)e * R * N;
+  // This block's tiles: XCD x = blockIdx % 8 owns a contiguous range of tiles; its
+  // blocks take them round-robin, so at any time they work on neighbouring tiles
+  // (row tile fastest: neighbours share a weight panel in that XCD's L2).
+  const int nb = gridDim.x;
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int xq = ntiles / kXcds, xr = ntiles % kXcds;
+  const int t_begin = xcd * xq + (xcd < xr ? xcd : xr);
+  const int t_end = t_begin + xq + (xcd < xr ? 1 : 0);
+  const int stride = (nb - xcd + kXcds - 1) / kXcds;           // blocks on this XCD
+  const int first = t_begin + slot;
+  const int my_tiles = first < t_end ? (t_end - first + stride - 1) / stride : 0;
+  const int G = my_tiles * KT;                                 // K steps of this block
+  if (G == 0) return;                                          // block-uniform
 
   // per-lane source byte offsets of the 4 + 4 copy instructions of this wavefront
   uint32_t a_voff[4], b_voff[4];
@@ -267,23 +284,26 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const int cb = (lane & 31) ^ (4 * (krow & 3));
     b_voff[q] = (uint32_t)((krow * N + 8 * cb) * 2);
   }
-#define MOE_DMA_ISSUE(TILE, STAGE)                                                           \
-  {                                                                                          \
-    const bf16_t* as_ = a_src + (size_t)(TILE) * BK;                                         \
-    const bf16_t* bs_ = b_src + (size_t)(TILE) * BK * N;                                     \
-    const uint32_t la_ = lds0 + (STAGE) * SM::kStage + wave * 4096;                          \
-    const uint32_t lb_ = la_ + SM::kAStage;                                                  \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q) MOE_DMA16(la_ + q * 1024, a_voff[q], as_); \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q) MOE_DMA16(lb_ + q * 1024, b_voff[q], bs_); \
-  }
 
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  // producer cursor: the next step to copy (tile p_tile, k step p_kt) and its sources
+  int p_tile = first, p_kt = 0, p_stage = 0, p_g = 0;
+  const bf16_t* p_a;
+  const bf16_t* p_b;
+#define MOE_DMA_SET_SOURCES()                                                                \
+  {                                                                                          \
+    const int e_ = p_tile / per_e, t_ = p_tile - e_ * per_e;                                 \
+    p_a = A + ((size_t)e_ * R + (size_t)(t_ % tiles_m) * BM) * K;                            \
+    p_b = B + (size_t)e_ * K * N + (size_t)(t_ / tiles_m) * BN;                              \
+  }
+#define MOE_DMA_ADVANCE()                                                                    \
+  {                                                                                          \
+    ++p_g;                                                                                   \
+    p_stage = p_stage + 1 == ST ? 0 : p_stage + 1;                                           \
+    p_a += BK;                                                                               \
+    p_b += (size_t)BK * N;                                                                   \
+    if (++p_kt == KT) { p_kt = 0; p_tile += stride; if (p_g < G) MOE_DMA_SET_SOURCES() }     \
+  }
+  MOE_DMA_SET_SOURCES()
 
   // fragment read offsets (bytes inside a stage)
   //   A: row wm0 + 32 i + lane%32, chunk 2 kk + lane/32 at its permuted position
@@ -306,84 +326,134 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
   typedef bf16x8_t __attribute__((address_space(3))) * lds_bf16x8_ptr;
   struct Frags { bf16x8_t a[TM]; bf16x8_t b[TN]; };
-#define MOE_DMA_READ_FRAGS(F, STAGE, kk)                                                     \
+#define MOE_DMA_READ_A(F, STAGE, kk, i)                                                      \
+  (F).a[i] = *(lds_bf16x8_ptr)(uintptr_t)(lds0 + (STAGE) * SM::kStage + a_rd[kk] + (i) * 32 * 64);
+#define MOE_DMA_READ_B(F, STAGE, kk, j)                                                      \
   {                                                                                          \
-    const uint32_t sb_ = lds0 + (STAGE) * SM::kStage;                                        \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-      (F).a[i] = *(lds_bf16x8_ptr)(uintptr_t)(sb_ + a_rd[kk] + i * 32 * 64);                 \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
-      const uint32_t pb_ = sb_ + b_rd[j] + (kk) * 16 * 512;                                  \
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pb_); \
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                            \
-          (lds_s16x4_ptr)(uintptr_t)(pb_ + 4 * 512));                                        \
-      (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                \
-                                    __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
-    }                                                                                        \
+    const uint32_t pb_ = lds0 + (STAGE) * SM::kStage + b_rd[j] + (kk) * 16 * 512;            \
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pb_); \
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                              \
+        (lds_s16x4_ptr)(uintptr_t)(pb_ + 4 * 512));                                          \
+    (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                  \
+                                  __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));  \
   }
-#define MOE_DMA_MFMA(F)                                                                      \
-  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                             \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((F).b[j], (F).a[i], acc[i][j], 0, 0, 0);
+  // The weight fragment goes in as the first MFMA operand: the 32x32 result is then
+  // the transposed tile, i.e. a lane owns 4 consecutive columns of one row of C.
+#define MOE_DMA_MFMA_ROW(F, i)                                                               \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j)                                             \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((F).b[j], (F).a[i], acc[i][j], 0, 0, 0);
 
-  const int KT = K / BK;
   Frags fr[2];
-  // wait until at most `younger` tiles (8 copies each) of this wavefront are still in flight
-#define MOE_DMA_WAIT(younger)                                                                \
-  {                                                                                          \
-    if ((younger) >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                    \
-    else if ((younger) == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                \
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                    \
+  // start the first ST-1 steps, wait for step 0
+  const int pro = ST - 1 < G ? ST - 1 : G;
+  for (int tl = 0; tl < pro; ++tl) {
+    const uint32_t la_ = lds0 + p_stage * SM::kStage + wave * 4096;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      MOE_DMA16(la_ + q * 1024, a_voff[q], p_a);
+      MOE_DMA16(la_ + SM::kAStage + q * 1024, b_voff[q], p_b);
+    }
+    MOE_DMA_ADVANCE()
   }
-  const int pro = ST - 1 < KT ? ST - 1 : KT;                   // tiles started up front
-  for (int tl = 0; tl < pro; ++tl) MOE_DMA_ISSUE(tl, tl)
-  MOE_DMA_WAIT(pro - 1)                                        // tile 0 has landed
+  if (pro >= 3) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (pro == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  MOE_DMA_READ_FRAGS(fr[0], 0, 0)
-  int stage = 0;                                               // stage of tile kt
-  // The fragment reads are unconditional (the last iteration fetches fragments nobody
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { MOE_DMA_READ_A(fr[0], 0, 0, i) MOE_DMA_READ_B(fr[0], 0, 0, i) }
+
+  int stage = 0, g = 0;                                        // consumer cursor
+  // The fragment reads are unconditional (the very last step fetches fragments nobody
   // multiplies, from a valid stage): a conditional read would make every later wait
   // for LDS data wait for all outstanding reads instead of the older ones only.
-  for (int kt = 0; kt < KT; ++kt) {
-    MOE_DMA_READ_FRAGS(fr[1], stage, 1)
-    MOE_DMA_MFMA(fr[0])
-    // tile kt+1 must be visible to everyone before its fragments are fetched
-    const int issued = kt + ST - 1 < KT ? kt + ST - 1 : KT;
-    const int need = kt + 1 < KT ? kt + 1 : KT - 1;
-    MOE_DMA_WAIT(issued - 1 - need)
-    __syncthreads();
-    const int nstage = stage + 1 == ST ? 0 : stage + 1;        // stage of tile kt+1
-    if (kt + ST - 1 < KT) {
-      const int fstage = stage == 0 ? ST - 1 : stage - 1;      // stage of tile kt-1, now free
-      MOE_DMA_ISSUE(kt + ST - 1, fstage)
-    }
-    MOE_DMA_READ_FRAGS(fr[0], nstage, 0)
-    MOE_DMA_MFMA(fr[1])
-    stage = nstage;
-  }
-#undef MOE_DMA_WAIT
+  for (int c_tile = first; c_tile < t_end; c_tile += stride) {
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // epilogue: acc[i][j][4 q + r] = C[32 i + lane%32][32 j + 8 q + 4 (lane/32) + r]
+    for (int kt = 0; kt < KT; ++kt, ++g) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm0 + 32 * i + (lane & 31);
+      for (int i = 0; i < TM; ++i) { MOE_DMA_READ_A(fr[1], stage, 1, i) MOE_DMA_READ_B(fr[1], stage, 1, i) }
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int i = 0; i < TM; ++i) { MOE_DMA_MFMA_ROW(fr[0], i) }
+      // The own copies of step g+1 must have landed; younger steps (8 copies each) may
+      // still fly.  p_g steps have been started.  Loads and stores do not complete in
+      // order with respect to each other, so after an epilogue everything is awaited.
+      // (The counts pass through an empty asm so that the optimiser cannot peel or
+      // duplicate the loop body around these conditions: copies of the body would shuffle
+      // the 256 accumulator registers between them.)
+      int younger = p_g - 1 - (g + 1 < G ? g + 1 : G - 1);
+      if (kt == 0 && g > 0) younger = 0;                       // stores of the previous tile
+      younger = __builtin_amdgcn_readfirstlane(younger);
+      asm volatile("" : "+s"(younger));
+      if (younger <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      __syncthreads();
+      const int nstage = stage + 1 == ST ? 0 : stage + 1;      // stage of step g+1
+      int more = __builtin_amdgcn_readfirstlane(p_g < G);      // p_stage: stage of step g-1, free now
+      asm volatile("" : "+s"(more));
+      const uint32_t la_ = lds0 + p_stage * SM::kStage + wave * 4096;
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn0 + 32 * j + 8 * q + 4 * (lane >> 5);
-        float v[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          v[r] = acc[i][j][4 * q + r];
-          if (RELU) v[r] = fmaxf(v[r], 0.f);
+        if (more) {
+          MOE_DMA16(la_ + q * 1024, a_voff[q], p_a);
+          MOE_DMA16(la_ + SM::kAStage + q * 1024, b_voff[q], p_b);
         }
-        *reinterpret_cast<uint2*>(Ce + (size_t)row * N + col) =
-            uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        MOE_DMA_READ_A(fr[0], nstage, 0, q)
+        MOE_DMA_READ_B(fr[0], nstage, 0, q)
+        MOE_DMA_MFMA_ROW(fr[1], q)
+        __builtin_amdgcn_sched_barrier(0);
       }
+      if (more) MOE_DMA_ADVANCE()
+      stage = nstage;
+    }
+
+    // Tile finished: acc[i][j][4 q + r] = C[32 i + r32][32 j + 8 q + 4 h + r], r32 = lane%32,
+    // h = lane/32.  The stage of the step just consumed is free until the next step's
+    // barrier, so each wavefront turns its tile through 8 KB of it, 32 rows at a time, into
+    // full-row 16-byte stores.  Staging layout: [32 rows][16 chunks of 16 bytes], chunk c of
+    // row r at position c ^ (r & 15), its two 8-byte halves swapped when r >= 16 (then the
+    // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
+    const int e = c_tile / per_e, t = c_tile - e * per_e;
+    const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+    bf16_t* Ce = Cout + ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
+    const uint32_t st_base = lds0 + (stage == 0 ? ST - 1 : stage - 1) * SM::kStage + wave * 8192;
+    const int r32 = lane & 31, hh = lane >> 5;
+    const uint32_t st_wr = st_base + r32 * 256 + 8 * (hh ^ (r32 >> 4));
+    typedef u32x2_t __attribute__((address_space(3))) * lds_u2_ptr;
+    typedef u32x4_t __attribute__((address_space(3))) * lds_u4_ptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint32_t lo = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+          uint32_t hi = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          if (RELU) { lo = relu_bf16x2(lo); hi = relu_bf16x2(hi); }
+          *(lds_u2_ptr)(uintptr_t)(st_wr + (((4 * j + q) ^ (r32 & 15)) * 16)) = u32x2_t{lo, hi};
+        }
+#pragma unroll
+      for (int ps = 0; ps < 8; ++ps) {
+        const int rr = 4 * ps + (lane >> 4), c = lane & 15;
+        u32x4_t d = *(lds_u4_ptr)(uintptr_t)(st_base + rr * 256 + ((c ^ (rr & 15)) * 16));
+        if (ps >= 4) d = u32x4_t{d[2], d[3], d[0], d[1]};      // rows 16..31: halves were swapped
+        *reinterpret_cast<u32x4_t*>(Ce + (size_t)(32 * i + rr) * N + 8 * c) = d;
+      }
+      __builtin_amdgcn_sched_barrier(0);   // one row group at a time: small register need
+    }
   }
-#undef MOE_DMA_ISSUE
-#undef MOE_DMA_READ_FRAGS
-#undef MOE_DMA_MFMA
+#undef MOE_DMA_SET_SOURCES
+#undef MOE_DMA_ADVANCE
+#undef MOE_DMA_READ_A
+#undef MOE_DMA_READ_B
+#undef MOE_DMA_MFMA_ROW
 }
 
 template <int ST, bool RELU>
@@ -392,17 +462,23 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   using SM = DmaSmem<ST>;
   auto kern = expert_gemm_bf16_dma_kernel<ST, RELU>;
   static bool attr_set = false;   // idempotent: a repeated call sets the same value
+  static int cus = 0;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytes) != hipSuccess)
       return MOE_EHIP;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      return MOE_EHIP;
     attr_set = true;
   }
   const int tiles_m = R / 256, tiles_n = N / 256;
-  const long long nblk = (long long)E * tiles_m * tiles_n;
-  if (nblk > 0x7fffffffLL) return MOE_EUNSUPPORTED;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), SM::kBytes, st, A, B, Cout, R, N, K,
-                     tiles_m, tiles_n, (int)nblk);
+  const long long ntiles = (long long)E * tiles_m * tiles_n;
+  if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
+  const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SM::kBytes, st, A, B, Cout, R, N, K, tiles_m,
+                     tiles_n, (int)ntiles);
   return check_launch();
 }
 
