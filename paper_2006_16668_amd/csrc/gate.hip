@@ -5,11 +5,11 @@
 //                       first choices / sampled second choices and the gate sums
 //   gate_scan_kernel    per group: exclusive scan of the chunk histograms over the
 //                       chunks (the running counters c_E of Algorithm 1 at chunk
-//                       boundaries), c1, mean gates m_E, l_aux, fill, empty slots
+//                       boundaries), c1, mean gates m_E, fill, empty slots
 //   gate_slots_kernel   per chunk: stable rank of every token among the earlier
 //                       tokens of its chunk with the same expert + the chunk base
 //                       = position in the expert buffer; capacity test; combine
-//                       weights; inverse map slot -> token
+//                       weights; inverse map slot -> token; l_aux
 //
 // bf16 activations take the MFMA form of the first kernel (gate_mfma_*): x is
 // exactly bf16, so with wg split into three bf16 terms (hi + mid + lo = all 24
@@ -278,8 +278,11 @@ __device__ __forceinline__ void gate_chunk_epilogue(
 #define MOE_GATE_MFMA(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16( \
     __builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B), C, 0, 0, 0)
 
-// Narrow gates (E <= 64): a wavefront owns 32 tokens and all experts; a block is
-// 128 tokens = two chunks.  x goes from global memory straight into the A operand.
+// Narrow gates (E <= 64): a block is one chunk of 64 tokens; wavefront w owns the
+// 32 tokens of half w&1 and half w>>1 of the feature dimension, all experts.  x goes
+// from global memory straight into the A operand (a lane reads 64 contiguous bytes of
+// its token row per 64-feature block), four blocks ahead of the multiply, so that a
+// chunk of only 64 tokens keeps enough bytes in flight; the two partial sums meet in LDS.
 template <int ET>
 __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
@@ -287,17 +290,19 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int Epad = 32 * ET, pitch = Epad + 1;
-  __shared__ float zs[128 * pitch];
+  constexpr int Epad = 32 * ET, pitch = Epad + 1, PD = 4;
+  __shared__ float zs[64 * pitch];
+  __shared__ float part[64 * pitch];
   __shared__ int hh[2 * Epad];
-  const int npair = (nch + 1) / 2;
-  const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
+  const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int th = wave & 1, kh = wave >> 1;
   const int r = lane & 31, h = lane >> 5;
-  int s = pr * 128 + wave * 32 + r;
+  int s = ch * kChunk + th * 32 + r;
   s = s < S ? s : S - 1;                              // clamp: surplus rows are ignored later
-  const bf16_t* xrow = x + ((size_t)g * S + s) * M + 32 * h;
-  const int KB = (M + 63) / 64;
+  const bf16_t* xrow = x + ((size_t)g * S + s) * M;    // row start
+  const int KB = (M + 63) / 64, KB0 = (KB + 1) / 2;
+  const int kb0 = kh == 0 ? 0 : KB0, kb1 = kh == 0 ? KB0 : KB;
 
   f32x16_t acc[ET];
 #pragma unroll
@@ -305,50 +310,53 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-  uint4 a_cur[4], a_nxt[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-  {
-    a_cur[j] = uint4{0u, 0u, 0u, 0u};
-    if (32 * h + 8 * j < M) a_cur[j] = *reinterpret_cast<const uint4*>(xrow + 8 * j);
+  // Loads are unconditional: a block index past this wavefront's range is clamped (its
+  // data is never multiplied) and features past M read the row start instead (they meet
+  // zero weights in the packed operand).
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  u32x4_t a[PD][4];
+#define MOE_GATE_LOAD_X(P, KBI)                                                       \
+  _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                     \
+    int kbc_ = (KBI) < kb1 ? (KBI) : kb1 - 1;                                         \
+    kbc_ = kbc_ < 0 ? 0 : kbc_;                                                       \
+    const int col_ = kbc_ * 64 + 32 * h + 8 * j;                                      \
+    a[P][j] = *reinterpret_cast<const u32x4_t*>(xrow + (col_ < M ? col_ : 0));        \
   }
-  for (int kb = 0; kb < KB; ++kb) {
-    if (kb + 1 < KB) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int m = (kb + 1) * 64 + 32 * h + 8 * j;
-        a_nxt[j] = uint4{0u, 0u, 0u, 0u};
-        if (m < M) a_nxt[j] = *reinterpret_cast<const uint4*>(xrow + (kb + 1) * 64 + 8 * j);
+  for (int p = 0; p < PD; ++p) { MOE_GATE_LOAD_X(p, kb0 + p) }
+  for (int kb = kb0; kb < kb1; kb += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) {
+      const int cur = kb + p;
+      if (cur < kb1) {                                // wave-uniform
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint4* bp = wgP + (size_t)((cur * 4 + j) * ET) * 3 * 64 + lane;
+#pragma unroll
+          for (int t = 0; t < ET; ++t) {
+            const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
+            acc[t] = MOE_GATE_MFMA(a[p][j], b2, acc[t]);
+            acc[t] = MOE_GATE_MFMA(a[p][j], b1, acc[t]);
+            acc[t] = MOE_GATE_MFMA(a[p][j], b0, acc[t]);
+          }
+        }
       }
+      MOE_GATE_LOAD_X(p, cur + PD)
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint4* bp = wgP + (size_t)((kb * 4 + j) * ET) * 3 * 64 + lane;
-#pragma unroll
-      for (int t = 0; t < ET; ++t) {
-        const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
-        acc[t] = MOE_GATE_MFMA(a_cur[j], b2, acc[t]);
-        acc[t] = MOE_GATE_MFMA(a_cur[j], b1, acc[t]);
-        acc[t] = MOE_GATE_MFMA(a_cur[j], b0, acc[t]);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) a_cur[j] = a_nxt[j];
   }
-  // acc[t][i]: token row 8 (i/4) + 4 h + i%4 of this wave, expert 32 t + r
+#undef MOE_GATE_LOAD_X
+  // acc[t][i]: token row 8 (i/4) + 4 h + i%4 of this wave's half, expert 32 t + r
+  float* dst = kh == 0 ? zs : part;
 #pragma unroll
   for (int t = 0; t < ET; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      zs[(wave * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[t][i];
+      dst[(th * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[t][i];
   __syncthreads();
-#pragma unroll 1
-  for (int c = 0; c < 2; ++c) {
-    const int ch = pr * 2 + c;
-    if (ch < nch)
-      gate_chunk_epilogue(zs + c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight,
-                          gates_opt, hist1, hist2, msum, hh, hh + Epad);
-  }
+  for (int i = threadIdx.x; i < 64 * pitch; i += 256) zs[i] += part[i];
+  __syncthreads();
+  gate_chunk_epilogue(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt, hist1,
+                      hist2, msum, hh, hh + Epad);
 }
 
 // Wide gates (64 < E <= 512): the four wavefronts of a block share 128 tokens
@@ -449,43 +457,62 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
 }
 #undef MOE_GATE_MFMA
 
-// One block per group.  hist1/hist2 are replaced by their exclusive prefix over
-// chunks; hist2's prefix starts at c1 (second choices queue behind all first ones).
+// One block per (group, 32 experts); thread (e, k) owns expert e and the k-th of 8
+// contiguous segments of the chunk axis.  hist1/hist2 are replaced by their exclusive
+// prefix over chunks; hist2's prefix starts at c1 (second choices queue behind all first
+// choices).  Two passes over the segment (sum, then prefix) with a tiny LDS scan between.
 __global__ __launch_bounds__(256) void gate_scan_kernel(
     int S, int E, int C, int G, int nch,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, const float* __restrict__ msum,
     int32_t* __restrict__ c1, float* __restrict__ mean_gate, int32_t* __restrict__ fill,
-    int32_t* __restrict__ src_token, float* __restrict__ aux) {
-  __shared__ float red[256];
-  const int g = blockIdx.x;
-  float part = 0.f;
-  for (int e = threadIdx.x; e < E; e += 256) {
-    int run1 = 0, run2 = 0;
-    float ms = 0.f;
-    for (int ch = 0; ch < nch; ++ch) {
+    int32_t* __restrict__ src_token) {
+  __shared__ int t1[8][32], t2[8][32];
+  __shared__ float tm[8][32];
+  const int etiles = (E + 31) / 32;
+  const int g = blockIdx.x / etiles, e = (blockIdx.x % etiles) * 32 + (threadIdx.x & 31);
+  const int k = threadIdx.x >> 5;
+  const int seg = (nch + 7) / 8;
+  const int ch0 = k * seg, ch1 = (ch0 + seg < nch) ? ch0 + seg : nch;
+  const bool live = e < E;
+  int s1 = 0, s2 = 0;
+  float ms = 0.f;
+  if (live)
+    for (int ch = ch0; ch < ch1; ++ch) {
       const size_t i = ((size_t)g * nch + ch) * E + e;
-      const int a = hist1[i]; hist1[i] = run1; run1 += a;
-      const int b = hist2[i]; hist2[i] = run2; run2 += b;
+      s1 += hist1[i];
+      s2 += hist2[i];
       ms += msum[i];
     }
-    for (int ch = 0; ch < nch; ++ch) hist2[((size_t)g * nch + ch) * E + e] += run1;
-    const float mg = ms / (float)S;
-    c1[(size_t)g * E + e] = run1;
-    mean_gate[(size_t)g * E + e] = mg;
-    const long long tot = (long long)run1 + run2;
-    const int f = tot < C ? (int)tot : C;
-    fill[(size_t)g * E + e] = f;
-    int32_t* st = src_token + ((size_t)e * G + g) * C;
-    for (int c = f; c < C; ++c) st[c] = -1;
-    part += ((float)run1 / (float)S) * mg;
-  }
-  red[threadIdx.x] = part;
+  t1[k][threadIdx.x & 31] = s1;
+  t2[k][threadIdx.x & 31] = s2;
+  tm[k][threadIdx.x & 31] = ms;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
-    __syncthreads();
+  if (!live) return;
+  int base1 = 0, base2 = 0, tot1 = 0, tot2 = 0;
+  float mtot = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const int a = t1[kk][threadIdx.x & 31], b = t2[kk][threadIdx.x & 31];
+    if (kk < k) { base1 += a; base2 += b; }
+    tot1 += a;
+    tot2 += b;
+    mtot += tm[kk][threadIdx.x & 31];
   }
-  if (threadIdx.x == 0) aux[g] = red[0] / (float)E;
+  int run1 = base1, run2 = base2 + tot1;
+  for (int ch = ch0; ch < ch1; ++ch) {
+    const size_t i = ((size_t)g * nch + ch) * E + e;
+    const int a = hist1[i]; hist1[i] = run1; run1 += a;
+    const int b = hist2[i]; hist2[i] = run2; run2 += b;
+  }
+  const long long tot = (long long)tot1 + tot2;
+  const int f = tot < C ? (int)tot : C;
+  if (k == 0) {
+    c1[(size_t)g * E + e] = tot1;
+    mean_gate[(size_t)g * E + e] = mtot / (float)S;
+    fill[(size_t)g * E + e] = f;
+  }
+  int32_t* st = src_token + ((size_t)e * G + g) * C;
+  for (int c = f + k; c < C; c += 8) st[c] = -1;
 }
 
 // One wavefront per chunk.
@@ -493,9 +520,18 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
     int S, int E, int C, int G, int nch,
     const int32_t* __restrict__ base1, const int32_t* __restrict__ base2,
     const int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot,
-    float* __restrict__ weight, int32_t* __restrict__ src_token) {
+    float* __restrict__ weight, int32_t* __restrict__ src_token,
+    const int32_t* __restrict__ c1, const float* __restrict__ mean_gate, float* __restrict__ aux) {
   const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
   const int lane = threadIdx.x;
+  if (ch == 0) {
+    // l_aux[g] = (1/E) sum_e (c1/S) m_e, summed in a fixed order (lane-strided, then a tree)
+    float part = 0.f;
+    for (int e = lane; e < E; e += 64)
+      part += ((float)c1[(size_t)g * E + e] / (float)S) * mean_gate[(size_t)g * E + e];
+    part = wave_sum(part);
+    if (lane == 0) aux[g] = part / (float)E;
+  }
   const int s = ch * kChunk + lane;
   const bool valid = s < S;
   const size_t n = (size_t)g * S + (valid ? s : 0);
@@ -596,11 +632,11 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
     hipLaunchKernelGGL(gate_pack_wg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        wg, wgP, c.M, c.E, pg.T, total);
     if ((rc = check_launch()) != MOE_OK) return rc;
-    const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), block(256);
+    const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), grid_rows((unsigned)(c.G * nch)), block(256);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
-    if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, 0, st, MOE_GATE_ARGS);
+    if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid_rows, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid_rows, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 128) hipLaunchKernelGGL(gate_mfma_cols_kernel<1>, grid, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 256) hipLaunchKernelGGL(gate_mfma_cols_kernel<2>, grid, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 384) hipLaunchKernelGGL(gate_mfma_cols_kernel<3>, grid, block, 0, st, MOE_GATE_ARGS);
@@ -609,11 +645,12 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
     rc = check_launch();
   }
   if (rc != MOE_OK) return rc;
-  hipLaunchKernelGGL(gate_scan_kernel, dim3((unsigned)c.G), dim3(256), 0, st, c.S, c.E, c.C, c.G,
-                     nch, hist1, hist2, msum, c1, mean_gate, fill, src_token, aux);
+  hipLaunchKernelGGL(gate_scan_kernel, dim3((unsigned)(c.G * ((c.E + 31) / 32))), dim3(256), 0, st,
+                     c.S, c.E, c.C, c.G, nch, hist1, hist2, msum, c1, mean_gate, fill, src_token);
   if ((rc = check_launch()) != MOE_OK) return rc;
   hipLaunchKernelGGL(gate_slots_kernel, dim3((unsigned)(c.G * nch)), dim3(64), 0, st, c.S, c.E,
-                     c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token);
+                     c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token, c1,
+                     mean_gate, aux);
   return check_launch();
 }
 
