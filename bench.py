@@ -24,6 +24,14 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch of the expert GEMMs on the `paper` workload, from two
+# rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come
+# from a plain 1 GiB copy in the same runs).  Summary: profiles/moe_forward_paper_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {
+    "paper": {"expert_gemm1": (943690 * 2.0 + 1048600) * 1024,
+              "expert_gemm2": (789600 * 2.0 + 131070) * 1024},
+}
+
 
 def cpu_baseline(cfg, inp, seconds_hint=20.0):
     """The oracle as it stands, on whole groups of the same workload (groups are
@@ -60,6 +68,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (yardstick for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters); not part of the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the layer on ONE GPU (one device's share of tokens); "
@@ -90,6 +101,13 @@ def main():
     torch.cuda.synchronize()
     kept_rows = int(fill.sum().item())
     padded_rows = cfg.E * cfg.G * cfg.C
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     K, W = args.steps, args.warmup
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
@@ -131,7 +149,8 @@ def main():
                    "tokens": cfg.N, "kept_rows": kept_rows, "padded_rows": padded_rows},
         "roofline": {"bound": "mfma", "kernel": f"expert_gemm_bf16_dma_kernel ({dom})",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
                      "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
         "stages_ms": stage_ms,
         "stages_hbm_frac": {n: hbm_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS
