@@ -206,45 +206,47 @@ __device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
 }
 
 // Softmax / top-2 / random routing / chunk statistics for the 64 tokens of one
-// chunk whose logits sit in LDS (zs, row pitch `pitch` floats).  256 threads:
-// four per token, expert e handled by thread e % 4 of the token's quad.
+// chunk whose logits sit in LDS (zs, row pitch `pitch` floats).  NT threads:
+// TPT = NT/64 per token, expert e handled by thread e % TPT of the token's group.
 // Must be called by all threads of the block; ends with a barrier.
+template <int NT>
 __device__ __forceinline__ void gate_chunk_epilogue(
     float* zs, int pitch, int g, int ch, int S, int E, int nch, const float* __restrict__ u,
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt, int32_t* __restrict__ hist1, int32_t* __restrict__ hist2,
     float* __restrict__ msum, int* h1, int* h2) {
+  constexpr int TPT = NT / 64;
   const int tid = threadIdx.x;
-  for (int e = tid; e < E; e += 256) { h1[e] = 0; h2[e] = 0; }
+  for (int e = tid; e < E; e += NT) { h1[e] = 0; h2[e] = 0; }
   __syncthreads();
-  const int tk = tid >> 2, sub = tid & 3;
+  const int tk = tid / TPT, sub = tid % TPT;
   const int s = ch * kChunk + tk;
   const bool valid = s < S;
   const size_t n = (size_t)g * S + (valid ? s : 0);
   float* zr = zs + (size_t)tk * pitch;
   Top2 t2{-INFINITY, INT_MAX, -INFINITY, INT_MAX};
-  for (int e = sub; e < E; e += 4) {
+  for (int e = sub; e < E; e += TPT) {
     const float z = zr[e];
     if (better(z, e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z; t2.e1 = e; }
     else if (better(z, e, t2.v2, t2.e2)) { t2.v2 = z; t2.e2 = e; }
   }
 #pragma unroll
-  for (int o = 1; o <= 2; o <<= 1) {
+  for (int o = 1; o < TPT; o <<= 1) {
     Top2 other;
     other.v1 = __shfl_xor(t2.v1, o, 64); other.e1 = __shfl_xor(t2.e1, o, 64);
     other.v2 = __shfl_xor(t2.v2, o, 64); other.e2 = __shfl_xor(t2.e2, o, 64);
     t2 = top2_merge(t2, other);
   }
   float psum = 0.f;
-  for (int e = sub; e < E; e += 4) {
+  for (int e = sub; e < E; e += TPT) {
     const float p = expf(zr[e] - t2.v1);
     zr[e] = p;
     psum += p;
   }
-  psum += __shfl_xor(psum, 1, 64);
-  psum += __shfl_xor(psum, 2, 64);
+#pragma unroll
+  for (int o = 1; o < TPT; o <<= 1) psum += __shfl_xor(psum, o, 64);
   const float inv = 1.0f / psum;
-  for (int e = sub; e < E; e += 4) {
+  for (int e = sub; e < E; e += TPT) {
     const float gate = zr[e] * inv;
     zr[e] = gate;
     if (gates_opt != nullptr && valid) gates_opt[n * E + e] = gate;
@@ -265,7 +267,7 @@ __device__ __forceinline__ void gate_chunk_epilogue(
   __syncthreads();
   const int nv = min(kChunk, S - ch * kChunk);     // valid tokens of this chunk
   const size_t base = ((size_t)g * nch + ch) * E;
-  for (int e = tid; e < E; e += 256) {
+  for (int e = tid; e < E; e += NT) {
     float tot = 0.f;
     for (int r = 0; r < nv; ++r) tot += zs[(size_t)r * pitch + e];
     msum[base + e] = tot;
@@ -355,20 +357,23 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
   __syncthreads();
   for (int i = threadIdx.x; i < 64 * pitch; i += 256) zs[i] += part[i];
   __syncthreads();
-  gate_chunk_epilogue(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt, hist1,
-                      hist2, msum, hh, hh + Epad);
+  gate_chunk_epilogue<256>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+                           hist1, hist2, msum, hh, hh + Epad);
 }
 
-// Wide gates (64 < E <= 512): the four wavefronts of a block share 128 tokens
-// (staged through LDS) and each owns ETW column tiles of 32 experts.
-template <int ETW>
-__global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
+// Wide gates (64 < E <= 512): the NW wavefronts of a block share 128 tokens (staged
+// through LDS, double buffered) and each owns ETW column tiles of 32 experts.  The
+// packed weights go from L2 straight into the B operand; the loads of MFMA step ks+1
+// are issued before the multiplies of step ks.
+template <int ETW, int NW>
+__global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
     int S, int M, int E, int nch,
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int Epad = 128 * ETW, T = 4 * ETW, pitch = Epad + 1;
+  constexpr int NT = 64 * NW, T = ETW * NW, Epad = 32 * T, pitch = Epad + 1;
+  constexpr int AV = 1024 / NT;                        // 16-byte vectors of x per thread and block
   constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
   constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
   constexpr int kZBytes = 64 * pitch * 4;              // logits of one chunk
@@ -377,6 +382,7 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
   __shared__ int hh[2 * Epad];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);
   float* zs = reinterpret_cast<float*>(smem);
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
   const int npair = (nch + 1) / 2;
   const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
@@ -384,20 +390,26 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
   const int r = lane & 31, h = lane >> 5;
   const int KB = (M + 63) / 64;
 
-  // cooperative A loads: 128 rows x 64 features = 1024 16-byte vectors, 4 per thread
-  const int lrow = tid >> 3, lvec = tid & 7;           // rows lrow + 32 i
-  const bf16_t* xg = x + (size_t)g * S * M + lvec * 8;
-  uint4 areg[4];
-  auto row_of = [&](int i) { int s = pr * 128 + lrow + 32 * i; return s < S ? s : S - 1; };
+  // cooperative x loads: 128 rows x 64 features = 1024 16-byte vectors per block of features;
+  // rows past S are clamped (never used), features past M read the row start (zero weights)
+  const int lrow = tid >> 3, lvec = tid & 7;           // rows lrow + (NT/8) i
+  const bf16_t* xrow[AV];
+#pragma unroll
+  for (int i = 0; i < AV; ++i) {
+    int s = pr * 128 + lrow + (NT / 8) * i;
+    s = s < S ? s : S - 1;
+    xrow[i] = x + ((size_t)g * S + s) * M;
+  }
+  u32x4_t areg[AV];
 #define MOE_GATE_LOAD_A(kb)                                                              \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                        \
-    const int m = (kb) * 64 + lvec * 8;                                                  \
-    areg[i] = uint4{0u, 0u, 0u, 0u};                                                     \
-    if (m < M) areg[i] = *reinterpret_cast<const uint4*>(xg + (size_t)row_of(i) * M + (kb) * 64); \
+  _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                       \
+    const int col_ = (kb) * 64 + lvec * 8;                                               \
+    areg[i] = *reinterpret_cast<const u32x4_t*>(xrow[i] + (col_ < M ? col_ : 0));        \
   }
 #define MOE_GATE_STORE_A(buf)                                                            \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                          \
-    *reinterpret_cast<uint4*>(As + (buf) * 128 * kAPitch + (lrow + 32 * i) * kAPitch + lvec * 8) = areg[i];
+  _Pragma("unroll") for (int i = 0; i < AV; ++i)                                         \
+    *reinterpret_cast<u32x4_t*>(As + (buf) * 128 * kAPitch +                             \
+                                (lrow + (NT / 8) * i) * kAPitch + lvec * 8) = areg[i];
 
   f32x16_t acc[4][ETW];
 #pragma unroll
@@ -407,8 +419,20 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
 
+  // B operand of MFMA step ks (= 4 kb + j), column tile t, split sp
+  const u32x4_t* bbase = reinterpret_cast<const u32x4_t*>(wgP) + (size_t)wave * ETW * 3 * 64 + lane;
+  const int KS = 4 * KB;
+  u32x4_t bq[2][ETW * 3];
+#define MOE_GATE_LOAD_B(P, ks)                                                           \
+  {                                                                                      \
+    const int ksc_ = (ks) < KS ? (ks) : KS - 1;                                          \
+    _Pragma("unroll") for (int q = 0; q < ETW * 3; ++q)                                  \
+      bq[P][q] = bbase[((size_t)ksc_ * T * 3 + q) * 64];                                 \
+  }
+
   MOE_GATE_LOAD_A(0)
   MOE_GATE_STORE_A(0)
+  MOE_GATE_LOAD_B(0, 0)
   __syncthreads();
   for (int kb = 0; kb < KB; ++kb) {
     const int cur = kb & 1;
@@ -416,27 +440,26 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
     const bf16_t* as = As + cur * 128 * kAPitch + r * kAPitch + 32 * h;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      uint4 af[4];
+      MOE_GATE_LOAD_B((j + 1) & 1, kb * 4 + j + 1)
+      u32x4_t af[4];
 #pragma unroll
       for (int rt = 0; rt < 4; ++rt)
-        af[rt] = *reinterpret_cast<const uint4*>(as + rt * 32 * kAPitch + 8 * j);
-      const uint4* bp = wgP + ((size_t)(kb * 4 + j) * T + wave * ETW) * 3 * 64 + lane;
+        af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
 #pragma unroll
-      for (int t = 0; t < ETW; ++t) {
-        const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
+      for (int t = 0; t < ETW; ++t)
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt) {
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], b2, acc[rt][t]);
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], b1, acc[rt][t]);
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], b0, acc[rt][t]);
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 2], acc[rt][t]);
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 1], acc[rt][t]);
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 0], acc[rt][t]);
         }
-      }
     }
     if (kb + 1 < KB) { MOE_GATE_STORE_A(cur ^ 1) }
     __syncthreads();
   }
 #undef MOE_GATE_LOAD_A
 #undef MOE_GATE_STORE_A
+#undef MOE_GATE_LOAD_B
   // the A stages are dead from here on; the same LDS holds one chunk of logits at a time
 #pragma unroll 1
   for (int c = 0; c < 2; ++c) {
@@ -451,8 +474,8 @@ __global__ __launch_bounds__(256) void gate_mfma_cols_kernel(
           zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
               c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
     __syncthreads();
-    gate_chunk_epilogue(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt, hist1,
-                        hist2, msum, hh, hh + Epad);
+    gate_chunk_epilogue<NT>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+                            hist1, hist2, msum, hh, hh + Epad);
   }
 }
 #undef MOE_GATE_MFMA
@@ -597,7 +620,7 @@ struct PackGeom { int T, KS; size_t bytes; };
 static PackGeom pack_geom(const moe_config& c) {
   PackGeom p{};
   if (c.act_dtype != MOE_BF16 || c.E > 512) return p;   // bytes == 0: plain kernel
-  const int epad = c.E <= 64 ? (c.E + 31) / 32 * 32 : (c.E + 127) / 128 * 128;
+  const int epad = c.E <= 64 ? (c.E + 31) / 32 * 32 : c.E <= 128 ? 128 : c.E <= 256 ? 256 : 512;
   p.T = epad / 32;
   p.KS = (c.M + 63) / 64 * 4;
   p.bytes = (size_t)p.KS * p.T * 3 * 64 * 16;
@@ -637,10 +660,9 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
     if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid_rows, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid_rows, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 128) hipLaunchKernelGGL(gate_mfma_cols_kernel<1>, grid, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 256) hipLaunchKernelGGL(gate_mfma_cols_kernel<2>, grid, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 384) hipLaunchKernelGGL(gate_mfma_cols_kernel<3>, grid, block, 0, st, MOE_GATE_ARGS);
-    else hipLaunchKernelGGL(gate_mfma_cols_kernel<4>, grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_kernel<1, 4>), grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 4>), grid, block, 0, st, MOE_GATE_ARGS);
+    else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
 #undef MOE_GATE_ARGS
     rc = check_launch();
   }
