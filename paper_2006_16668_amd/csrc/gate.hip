@@ -216,6 +216,7 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     float* __restrict__ gates_opt, int32_t* __restrict__ hist1, int32_t* __restrict__ hist2,
     float* __restrict__ msum, int* h1, int* h2) {
   constexpr int TPT = NT / 64;
+  __shared__ float rinv[kChunk];
   const int tid = threadIdx.x;
   for (int e = tid; e < E; e += NT) { h1[e] = 0; h2[e] = 0; }
   __syncthreads();
@@ -237,20 +238,21 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     other.v2 = __shfl_xor(t2.v2, o, 64); other.e2 = __shfl_xor(t2.e2, o, 64);
     t2 = top2_merge(t2, other);
   }
+  // softmax numerators stay in LDS; the reciprocal of the row sum goes to rinv[] and is
+  // applied when the chunk's gate sums are formed (bulk exponentials: the hardware
+  // exp2 path, relative error ~1e-6 at most over the range a softmax tail can reach)
   float psum = 0.f;
   for (int e = sub; e < E; e += TPT) {
-    const float p = expf(zr[e] - t2.v1);
+    const float p = __expf(zr[e] - t2.v1);
     zr[e] = p;
     psum += p;
   }
 #pragma unroll
   for (int o = 1; o < TPT; o <<= 1) psum += __shfl_xor(psum, o, 64);
   const float inv = 1.0f / psum;
-  for (int e = sub; e < E; e += TPT) {
-    const float gate = zr[e] * inv;
-    zr[e] = gate;
-    if (gates_opt != nullptr && valid) gates_opt[n * E + e] = gate;
-  }
+  if (sub == 0) rinv[tk] = valid ? inv : 0.f;
+  if (gates_opt != nullptr && valid)
+    for (int e = sub; e < E; e += TPT) gates_opt[n * E + e] = zr[e] * inv;
   if (sub == 0 && valid) {
     const float p2 = expf(t2.v2 - t2.v1);
     const float g1n = 1.0f / (1.0f + p2);
@@ -265,12 +267,18 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     if (sampled) atomicAdd(&h2[t2.e2], 1);
   }
   __syncthreads();
-  const int nv = min(kChunk, S - ch * kChunk);     // valid tokens of this chunk
   const size_t base = ((size_t)g * nch + ch) * E;
   for (int e = tid; e < E; e += NT) {
-    float tot = 0.f;
-    for (int r = 0; r < nv; ++r) tot += zs[(size_t)r * pitch + e];
-    msum[base + e] = tot;
+    // fixed summation order: eight interleaved partial sums over the 64 rows, then a tree
+    // (rows past the end of the group carry rinv = 0)
+    float part[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) part[q] = 0.f;
+#pragma unroll
+    for (int r0 = 0; r0 < kChunk; r0 += 8)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) part[q] = fmaf(zs[(size_t)(r0 + q) * pitch + e], rinv[r0 + q], part[q]);
+    msum[base + e] = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
     hist1[base + e] = h1[e];
     hist2[base + e] = h2[e];
   }
@@ -363,9 +371,8 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
 
 // Wide gates (64 < E <= 512): the NW wavefronts of a block share 128 tokens (staged
 // through LDS, double buffered) and each owns ETW column tiles of 32 experts.  The
-// packed weights go from L2 straight into the B operand; the loads of MFMA step ks+1
-// are issued before the multiplies of step ks.
-template <int ETW, int NW>
+// packed weights go from L2 straight into the B operand, PB MFMA steps ahead of their use.
+template <int ETW, int NW, int PB>
 __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
     int S, int M, int E, int nch,
@@ -400,17 +407,6 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
     s = s < S ? s : S - 1;
     xrow[i] = x + ((size_t)g * S + s) * M;
   }
-  u32x4_t areg[AV];
-#define MOE_GATE_LOAD_A(kb)                                                              \
-  _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                       \
-    const int col_ = (kb) * 64 + lvec * 8;                                               \
-    areg[i] = *reinterpret_cast<const u32x4_t*>(xrow[i] + (col_ < M ? col_ : 0));        \
-  }
-#define MOE_GATE_STORE_A(buf)                                                            \
-  _Pragma("unroll") for (int i = 0; i < AV; ++i)                                         \
-    *reinterpret_cast<u32x4_t*>(As + (buf) * 128 * kAPitch +                             \
-                                (lrow + (NT / 8) * i) * kAPitch + lvec * 8) = areg[i];
-
   f32x16_t acc[4][ETW];
 #pragma unroll
   for (int rt = 0; rt < 4; ++rt)
@@ -419,44 +415,66 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
 
-  // B operand of MFMA step ks (= 4 kb + j), column tile t, split sp
+  // B operand of MFMA step ks (= 4 kb + j), column tile t, split sp: ring of four register
+  // sets, slot ks & 3, filled PB steps ahead of its use
   const u32x4_t* bbase = reinterpret_cast<const u32x4_t*>(wgP) + (size_t)wave * ETW * 3 * 64 + lane;
   const int KS = 4 * KB;
-  u32x4_t bq[2][ETW * 3];
+  u32x4_t bq[4][ETW * 3];
 #define MOE_GATE_LOAD_B(P, ks)                                                           \
   {                                                                                      \
     const int ksc_ = (ks) < KS ? (ks) : KS - 1;                                          \
     _Pragma("unroll") for (int q = 0; q < ETW * 3; ++q)                                  \
       bq[P][q] = bbase[((size_t)ksc_ * T * 3 + q) * 64];                                 \
   }
-
-  MOE_GATE_LOAD_A(0)
-  MOE_GATE_STORE_A(0)
-  MOE_GATE_LOAD_B(0, 0)
-  __syncthreads();
-  for (int kb = 0; kb < KB; ++kb) {
-    const int cur = kb & 1;
-    if (kb + 1 < KB) { MOE_GATE_LOAD_A(kb + 1) }
-    const bf16_t* as = As + cur * 128 * kAPitch + r * kAPitch + 32 * h;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      MOE_GATE_LOAD_B((j + 1) & 1, kb * 4 + j + 1)
-      u32x4_t af[4];
-#pragma unroll
-      for (int rt = 0; rt < 4; ++rt)
-        af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
-#pragma unroll
-      for (int t = 0; t < ETW; ++t)
-#pragma unroll
-        for (int rt = 0; rt < 4; ++rt) {
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 2], acc[rt][t]);
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 1], acc[rt][t]);
-          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j & 1][t * 3 + 0], acc[rt][t]);
-        }
-    }
-    if (kb + 1 < KB) { MOE_GATE_STORE_A(cur ^ 1) }
-    __syncthreads();
+  // x: stage kb & 1 of LDS is multiplied while blocks kb+1 .. kb+3 sit in (or fly to)
+  // register sets (kb+1)&3 .. (kb+3)&3 and block kb+4 is requested into set kb & 3:
+  // a load has three iterations to land before it is written to LDS
+  u32x4_t areg[4][AV];
+#define MOE_GATE_LOAD_A(P, kb)                                                           \
+  _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                       \
+    const int kbc_ = (kb) < KB ? (kb) : KB - 1;                                          \
+    const int col_ = kbc_ * 64 + lvec * 8;                                               \
+    areg[P][i] = *reinterpret_cast<const u32x4_t*>(xrow[i] + (col_ < M ? col_ : 0));     \
   }
+#define MOE_GATE_STORE_A(P, buf)                                                         \
+  _Pragma("unroll") for (int i = 0; i < AV; ++i)                                         \
+    *reinterpret_cast<u32x4_t*>(As + (buf) * 128 * kAPitch +                             \
+                                (lrow + (NT / 8) * i) * kAPitch + lvec * 8) = areg[P][i];
+#define MOE_GATE_KBLOCK(kb, Q) /* Q = kb & 3 */                                          \
+  {                                                                                      \
+    MOE_GATE_LOAD_A(Q, (kb) + 4)                                                         \
+    const bf16_t* as = As + ((Q) & 1) * 128 * kAPitch + r * kAPitch + 32 * h;            \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                      \
+      MOE_GATE_LOAD_B((j + PB) & 3, (kb) * 4 + j + PB)                                   \
+      u32x4_t af[4];                                                                     \
+      _Pragma("unroll") for (int rt = 0; rt < 4; ++rt)                                   \
+        af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);      \
+      _Pragma("unroll") for (int t = 0; t < ETW; ++t)                                    \
+        _Pragma("unroll") for (int rt = 0; rt < 4; ++rt) {                               \
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 2], acc[rt][t]);              \
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 1], acc[rt][t]);              \
+          acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 0], acc[rt][t]);              \
+        }                                                                                \
+    }                                                                                    \
+    MOE_GATE_STORE_A(((Q) + 1) & 3, ((Q) + 1) & 1) /* block kb+1 (a clamped copy at the end) */ \
+    __syncthreads();                                                                     \
+  }
+
+  MOE_GATE_LOAD_A(0, 0)
+  MOE_GATE_STORE_A(0, 0)
+  MOE_GATE_LOAD_A(1, 1)
+  MOE_GATE_LOAD_A(2, 2)
+  MOE_GATE_LOAD_A(3, 3)
+#pragma unroll
+  for (int p = 0; p < PB; ++p) MOE_GATE_LOAD_B(p, p)
+  __syncthreads();
+  for (int kb = 0; kb < KB; kb += 4) {
+    MOE_GATE_KBLOCK(kb, 0)
+    if (kb + 1 < KB) MOE_GATE_KBLOCK(kb + 1, 1)
+    if (kb + 2 < KB) MOE_GATE_KBLOCK(kb + 2, 2)
+    if (kb + 3 < KB) MOE_GATE_KBLOCK(kb + 3, 3)
+  }
+#undef MOE_GATE_KBLOCK
 #undef MOE_GATE_LOAD_A
 #undef MOE_GATE_STORE_A
 #undef MOE_GATE_LOAD_B
@@ -660,9 +678,9 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
     if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid_rows, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid_rows, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_kernel<1, 4>), grid, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 4>), grid, block, 0, st, MOE_GATE_ARGS);
-    else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_kernel<1, 4, 3>), grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 4, 2>), grid, block, 0, st, MOE_GATE_ARGS);
+    else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
 #undef MOE_GATE_ARGS
     rc = check_launch();
   }
