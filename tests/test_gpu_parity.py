@@ -39,6 +39,13 @@ SMALL_CASES = [
     MoEConfig("e512", G=2, S=260, M=128, H=32, E=512, C=2, act_dtype="bf16", seed=23),
     MoEConfig("e600", G=1, S=100, M=64, H=32, E=600, C=1, act_dtype="bf16", seed=24),
     MoEConfig("e130_f32", G=1, S=150, M=48, H=32, E=130, C=3, act_dtype="f32", seed=25),
+    # exact 256x256 tiles (persistent copy-engine GEMM) with awkward tile counts: fewer tiles
+    # than XCDs, a tile count that is no multiple of 8, several row tiles, a single K step
+    MoEConfig("tiles_3", G=2, S=300, M=256, H=512, E=3, C=128, act_dtype="bf16", seed=26),
+    MoEConfig("tiles_rows", G=2, S=700, M=256, H=256, E=5, C=256, act_dtype="bf16", seed=27),
+    MoEConfig("one_k_step", G=1, S=600, M=32, H=256, E=4, C=256, act_dtype="bf16", seed=28),
+    MoEConfig("one_k_step_2", G=1, S=600, M=256, H=32, E=4, C=256, act_dtype="bf16", seed=29),
+    MoEConfig("many_tiles", G=2, S=1100, M=512, H=768, E=19, C=128, act_dtype="bf16", seed=30),
 ]
 
 
