@@ -140,12 +140,24 @@ int moe_forward(const moe_config* cfg, const void* x, const float* wg, const flo
                 void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Whether moe_forward folds the dispatch into the first expert GEMM for this config
+ * (Section 3.2's gather form: the GEMM's operand copies pick the rows of x through
+ * src_token, and the [E,G,C,M] buffer is never written).  It does so for bf16 layers
+ * with G*C % 256 == 0, H % 256 == 0, M % 32 == 0 and M >= 128; other shapes run the
+ * dispatch kernel.  The results are bit-identical either way.
+ * Pure host function: *fused = 1 or 0; returns MOE_OK or the config's error.
+ */
+int moe_forward_fuses_dispatch(const moe_config* cfg, int* fused);
+
+/*
  * moe_forward with stage timing marks, for callers that measure the kernels of
  * Algorithm 2 one by one.  Identical work on the same stream; in addition the
  * caller's MOE_FORWARD_EVENTS events (hipEvent_t handles created with timing
  * enabled; host array of handles) are recorded on `stream`:
  *   [0] start  [1] after gating  [2] after dispatch  [3] after h = relu(buf.wi)
  *   [4] after out = h.wo  [5] after combine.
+ * When the dispatch is folded into the first GEMM (moe_forward_fuses_dispatch), [2] is
+ * recorded directly after [1].
  * events == NULL is exactly moe_forward.  The events stay owned by the caller.
  */
 #define MOE_FORWARD_EVENTS 6

@@ -6,9 +6,11 @@
 There is no CPU fallback: a missing library raises on first use.
 """
 from .binding import (MoEError, MoEShape, library_path, load_library, moe_combine, moe_dispatch,
-                      moe_expert_ffn, moe_forward, moe_forward_events, moe_gate, moe_gate_workspace_bytes,
+                      moe_expert_ffn, moe_forward, moe_forward_events, moe_forward_fuses_dispatch,
+                      moe_gate, moe_gate_workspace_bytes,
                       moe_status_string, moe_workspace_bytes)
 
 __all__ = ["MoEError", "MoEShape", "library_path", "load_library", "moe_combine", "moe_dispatch",
-           "moe_expert_ffn", "moe_forward", "moe_forward_events", "moe_gate", "moe_gate_workspace_bytes",
+           "moe_expert_ffn", "moe_forward", "moe_forward_events", "moe_forward_fuses_dispatch",
+           "moe_gate", "moe_gate_workspace_bytes",
            "moe_status_string", "moe_workspace_bytes"]

@@ -21,7 +21,8 @@ MOE_F32, MOE_BF16 = 0, 1
 SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
-           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events")
+           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
+           "moe_forward_fuses_dispatch")
 FORWARD_EVENTS = 6
 
 
@@ -76,6 +77,7 @@ def load_library() -> ctypes.CDLL:
     for name, args in {
         "moe_gate_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_forward_fuses_dispatch": [cfgp, ctypes.POINTER(i32)],
         "moe_gate": [cfgp] + [vp] * 13 + [sz, vp],
         "moe_dispatch": [cfgp, vp, vp, vp, vp],
         "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
@@ -131,6 +133,14 @@ def moe_gate_workspace_bytes(shape: MoEShape) -> int:
     _check(load_library().moe_gate_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
            "moe_gate_workspace_bytes")
     return n.value
+
+
+def moe_forward_fuses_dispatch(shape: MoEShape) -> bool:
+    n = ctypes.c_int(0)
+    c = shape._c()
+    _check(load_library().moe_forward_fuses_dispatch(ctypes.byref(c), ctypes.byref(n)),
+           "moe_forward_fuses_dispatch")
+    return bool(n.value)
 
 
 def moe_workspace_bytes(shape: MoEShape) -> int:

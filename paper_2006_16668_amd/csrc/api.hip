@@ -22,7 +22,8 @@ int check_config(const moe_config* c) {
 
 // Layout of the moe_forward workspace.
 struct ForwardWs {
-  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, buf, h, out, gate_ws, total;
+  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, buf, h, out, gate_ws,
+      total;
 };
 
 ForwardWs carve(const moe_config& c) {
@@ -38,6 +39,7 @@ ForwardWs carve(const moe_config& c) {
   w.src_token = take(rows * 4);
   w.c1 = take(GE * 4);
   w.mean_gate = take(GE * 4);
+  w.zero_row = take((size_t)c.M * elt);
   w.buf = take(rows * c.M * elt);
   w.h = take(rows * c.H * elt);
   w.out = take(rows * c.M * elt);
@@ -77,6 +79,14 @@ int moe_workspace_bytes(const moe_config* cfg, size_t* bytes) {
   return MOE_OK;
 }
 
+int moe_forward_fuses_dispatch(const moe_config* cfg, int* fused) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (fused == nullptr) return MOE_EINVAL;
+  *fused = moe::expert_gemm1_can_gather(*cfg) ? 1 : 0;
+  return MOE_OK;
+}
+
 int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float* u,
              int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
              int32_t* src_token, int32_t* c1, float* mean_gate, float* aux, float* gates_opt,
@@ -89,7 +99,7 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
   if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
   if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
-                          mean_gate, aux, gates_opt, ws, static_cast<hipStream_t>(stream));
+                          mean_gate, aux, gates_opt, ws, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token, void* buf,
@@ -150,18 +160,23 @@ int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, co
   int32_t* slot = reinterpret_cast<int32_t*>(base + w.slot);
   float* weight = reinterpret_cast<float*>(base + w.weight);
   int32_t* src_token = reinterpret_cast<int32_t*>(base + w.src_token);
+  // bf16 layers whose shape the persistent GEMM takes skip the dispatched buffer: the first
+  // GEMM gathers its rows from x (then the dispatch mark coincides with the gate mark)
+  const bool gather = moe::expert_gemm1_can_gather(*cfg);
   if (!mark(0)) return MOE_EHIP;
   rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
                         reinterpret_cast<int32_t*>(base + w.fill), src_token,
                         reinterpret_cast<int32_t*>(base + w.c1),
                         reinterpret_cast<float*>(base + w.mean_gate), aux, nullptr,
-                        base + w.gate_ws, st);
+                        base + w.gate_ws, gather ? base + w.zero_row : nullptr, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
-  rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
+  if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
-  rc = moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
+  rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
+                                                base + w.h, st)
+              : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
   if (rc != MOE_OK) return rc;
   if (!mark(3)) return MOE_EHIP;
   rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);

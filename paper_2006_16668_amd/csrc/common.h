@@ -59,10 +59,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // host-side launchers (each returns a moe_status)
+// zero_row: NULL, or M bf16 elements that the gate also clears (see launch_expert_gemm1_gather)
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
-                float* gates_opt, void* ws, hipStream_t st);
+                float* gates_opt, void* ws, void* zero_row, hipStream_t st);
 size_t gate_workspace_bytes(const moe_config& c);
 int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token, void* buf,
                     hipStream_t st);
@@ -73,6 +74,11 @@ int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, vo
                         hipStream_t st);
 int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,
                         hipStream_t st);
+// h = relu(dispatch(x) . wi) without materialising the dispatched buffer: the GEMM's copies
+// gather the rows of x through src_token (zero_row: M zeros of the activation type).
+bool expert_gemm1_can_gather(const moe_config& c);
+int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
+                               const void* zero_row, const void* wi, void* h, hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 

@@ -243,10 +243,15 @@ struct DmaSmem {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"     \
                :: "s"(LDS_U32), "v"(VOFF_U32), "s"(SBASE) : "memory")
 
-template <int ST, bool RELU>
+// GATHER: the A rows are not a dense [E,R,K] buffer but rows of x picked by the dispatch
+// indices (A = x [G,S,K]; row r of expert e is x[r / C, src_token[e,r], :], a zero row when
+// the slot is empty), i.e. the dispatch of Algorithm 2 folded into the first GEMM's copies.
+template <int ST, bool RELU, bool GATHER>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
-    int R, int N, int K, int tiles_m, int tiles_n, int ntiles) {
+    int R, int N, int K, int tiles_m, int tiles_n, int ntiles,
+    const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
+    uint32_t c_magic, int c_shift) {
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -289,19 +294,60 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   int p_tile = first, p_kt = 0, p_stage = 0, p_g = 0;
   const bf16_t* p_a;
   const bf16_t* p_b;
+  // GATHER: per-lane source addresses of the 4 row copies.  The 64 dispatch indices of this
+  // wavefront's rows of a tile are copied to LDS (one more register-bypassing copy, issued
+  // 4 steps before the tile's first step, so the regular waits of the steps in between
+  // cover it) and read from there when the producer moves on to that tile.
+  uint64_t a_addr[4];
+  const uint32_t lds_tok = lds0 + (uint32_t)SM::kBytes + wave * 256;
+  typedef int __attribute__((address_space(3))) * lds_int_ptr;
+#define MOE_DMA_TOKENS(TILE)                                                                 \
+  {                                                                                          \
+    const int e_ = (TILE) / per_e, t_ = (TILE) - e_ * per_e;                                 \
+    const uint64_t ta_ = (uint64_t)(uintptr_t)(                                              \
+        src_token + (size_t)e_ * R + (size_t)(t_ % tiles_m) * BM + 64 * wave + lane);        \
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"            \
+                 :: "s"(lds_tok), "v"(ta_) : "memory");                                      \
+  }
+#define MOE_DMA_GATHER_ROWS(e_, m0_)                                                         \
+  {                                                                                          \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                          \
+      const int rl_ = 16 * q + (lane >> 2);                                                  \
+      const int tok_ = *(lds_int_ptr)(uintptr_t)(lds_tok + 4 * rl_);                         \
+      const int row_ = 64 * wave + rl_;                                                      \
+      const int ca_ = (lane & 3) ^ ((row_ >> 2) & 3);                                        \
+      const uint32_t n_ = (uint32_t)((m0_) + row_);                                          \
+      const uint32_t g_ = c_magic ? __umulhi(n_, c_magic) >> c_shift : n_;   /* n_ / C */    \
+      const bf16_t* src_ = tok_ >= 0 ? A + ((size_t)g_ * S + tok_) * K : zero_row;           \
+      a_addr[q] = (uint64_t)(uintptr_t)(src_ + 8 * ca_);                                     \
+    }                                                                                        \
+  }
+#define MOE_DMA16_ADDR(LDS_U32, ADDR_U64)                                                    \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"            \
+               :: "s"(LDS_U32), "v"(ADDR_U64) : "memory")
+#define MOE_DMA_COPY_A(LDS_U32, q)                                                           \
+  if (GATHER) { MOE_DMA16_ADDR(LDS_U32, a_addr[q]); } else { MOE_DMA16(LDS_U32, a_voff[q], p_a); }
 #define MOE_DMA_SET_SOURCES()                                                                \
   {                                                                                          \
     const int e_ = p_tile / per_e, t_ = p_tile - e_ * per_e;                                 \
-    p_a = A + ((size_t)e_ * R + (size_t)(t_ % tiles_m) * BM) * K;                            \
+    if (GATHER) MOE_DMA_GATHER_ROWS(e_, (t_ % tiles_m) * BM)                                 \
+    else p_a = A + ((size_t)e_ * R + (size_t)(t_ % tiles_m) * BM) * K;                       \
     p_b = B + (size_t)e_ * K * N + (size_t)(t_ / tiles_m) * BN;                              \
   }
 #define MOE_DMA_ADVANCE()                                                                    \
   {                                                                                          \
     ++p_g;                                                                                   \
     p_stage = p_stage + 1 == ST ? 0 : p_stage + 1;                                           \
-    p_a += BK;                                                                               \
+    if (GATHER) {                                                                            \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) a_addr[q] += BK * 2;                     \
+      if (p_kt == KT - 4 && p_tile + stride < t_end) MOE_DMA_TOKENS(p_tile + stride)         \
+    } else p_a += BK;                                                                        \
     p_b += (size_t)BK * N;                                                                   \
     if (++p_kt == KT) { p_kt = 0; p_tile += stride; if (p_g < G) MOE_DMA_SET_SOURCES() }     \
+  }
+  if (GATHER) {
+    MOE_DMA_TOKENS(first)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   MOE_DMA_SET_SOURCES()
 
@@ -350,7 +396,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const uint32_t la_ = lds0 + p_stage * SM::kStage + wave * 4096;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      MOE_DMA16(la_ + q * 1024, a_voff[q], p_a);
+      MOE_DMA_COPY_A(la_ + q * 1024, q)
       MOE_DMA16(la_ + SM::kAStage + q * 1024, b_voff[q], p_b);
     }
     MOE_DMA_ADVANCE()
@@ -402,7 +448,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (more) {
-          MOE_DMA16(la_ + q * 1024, a_voff[q], p_a);
+          MOE_DMA_COPY_A(la_ + q * 1024, q)
           MOE_DMA16(la_ + SM::kAStage + q * 1024, b_voff[q], p_b);
         }
         MOE_DMA_READ_A(fr[0], nstage, 0, q)
@@ -450,22 +496,37 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
   }
 #undef MOE_DMA_SET_SOURCES
+#undef MOE_DMA_GATHER_ROWS
+#undef MOE_DMA_TOKENS
+#undef MOE_DMA16_ADDR
+#undef MOE_DMA_COPY_A
 #undef MOE_DMA_ADVANCE
 #undef MOE_DMA_READ_A
 #undef MOE_DMA_READ_B
 #undef MOE_DMA_MFMA_ROW
 }
 
-template <int ST, bool RELU>
+template <int ST, bool RELU, bool GATHER>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
-                    hipStream_t st) {
+                    const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st) {
   using SM = DmaSmem<ST>;
-  auto kern = expert_gemm_bf16_dma_kernel<ST, RELU>;
+  constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0);
+  // n / C for n < 2^31 as (n * c_magic) >> (32 + c_shift), c_magic = ceil(2^(31+l) / C) with
+  // l = ceil(log2 C); C == 1 is flagged by c_magic == 0
+  uint32_t c_magic = 0;
+  int c_shift = 0;
+  if (GATHER && C > 1) {
+    int l = 0;
+    while ((1LL << l) < C) ++l;
+    c_magic = (uint32_t)((((unsigned long long)1 << (31 + l)) + C - 1) / C);
+    c_shift = l - 1;
+  }
+  auto kern = expert_gemm_bf16_dma_kernel<ST, RELU, GATHER>;
   static bool attr_set = false;   // idempotent: a repeated call sets the same value
   static int cus = 0;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytes) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
       return MOE_EHIP;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -477,9 +538,15 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   const long long ntiles = (long long)E * tiles_m * tiles_n;
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SM::kBytes, st, A, B, Cout, R, N, K, tiles_m,
-                     tiles_n, (int)ntiles);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
+                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift);
   return check_launch();
+}
+
+// shapes the persistent 256x256 kernel takes (its per-lane byte offsets are 32-bit)
+inline bool dma_shape_ok(int R, int N, int K) {
+  return R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && (long long)256 * K * 2 < (1LL << 31) &&
+         (long long)32 * N * 2 < (1LL << 31);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
@@ -513,10 +580,8 @@ int launch_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, in
 template <bool RELU>
 int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
               hipStream_t st) {
-  // per-lane byte offsets of the register-bypassing kernel are 32-bit
-  if (R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && (long long)256 * K * 2 < (1LL << 31) &&
-      (long long)32 * N * 2 < (1LL << 31))
-    return launch_bf16_dma<4, RELU>(A, B, Cout, E, R, N, K, st);
+  if (dma_shape_ok(R, N, K))
+    return launch_bf16_dma<4, RELU, false>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0, st);
   if (R > 128 && N >= 256) return launch_bf16<256, 256, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
   return launch_bf16<128, 128, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
 }
@@ -596,6 +661,21 @@ int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, vo
                           static_cast<float*>(h), c.E, R, c.H, c.M, st);
   return gemm_bf16<true>(static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(wi),
                          static_cast<bf16_t*>(h), c.E, R, c.H, c.M, st);
+}
+
+bool expert_gemm1_can_gather(const moe_config& c) {
+  const long long rows = (long long)c.G * c.C;
+  // the kernel fetches a tile's dispatch indices 4 K-steps (of 32) ahead of its first copy
+  return c.act_dtype == MOE_BF16 && rows <= 0x7fffffffLL && c.M >= 128 &&
+         dma_shape_ok((int)rows, c.H, c.M);
+}
+
+int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
+                               const void* zero_row, const void* wi, void* h, hipStream_t st) {
+  if (!expert_gemm1_can_gather(c)) return MOE_EUNSUPPORTED;
+  return launch_bf16_dma<4, true, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
+                                        static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
+                                        static_cast<const bf16_t*>(zero_row), c.S, c.C, st);
 }
 
 int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,

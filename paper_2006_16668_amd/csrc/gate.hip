@@ -562,9 +562,14 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
     const int32_t* __restrict__ base1, const int32_t* __restrict__ base2,
     const int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot,
     float* __restrict__ weight, int32_t* __restrict__ src_token,
-    const int32_t* __restrict__ c1, const float* __restrict__ mean_gate, float* __restrict__ aux) {
+    const int32_t* __restrict__ c1, const float* __restrict__ mean_gate, float* __restrict__ aux,
+    uint32_t* __restrict__ zero_fill, int zero_words) {
   const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
   const int lane = threadIdx.x;
+  // optional: clear the all-zero activation row that stands in for empty expert slots when
+  // the first expert GEMM gathers its rows from x
+  if (blockIdx.x == 0)
+    for (int i = lane; i < zero_words; i += 64) zero_fill[i] = 0u;
   if (ch == 0) {
     // l_aux[g] = (1/E) sum_e (c1/S) m_e, summed in a fixed order (lane-strided, then a tree)
     float part = 0.f;
@@ -653,7 +658,7 @@ size_t gate_workspace_bytes(const moe_config& c) {
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
-                float* gates_opt, void* ws, hipStream_t st) {
+                float* gates_opt, void* ws, void* zero_row, hipStream_t st) {
   const int nch = (c.S + kChunk - 1) / kChunk;
   const size_t seg = align_up((size_t)c.G * nch * c.E * 4, 256);
   int32_t* hist1 = reinterpret_cast<int32_t*>(ws);
@@ -690,7 +695,8 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
   if ((rc = check_launch()) != MOE_OK) return rc;
   hipLaunchKernelGGL(gate_slots_kernel, dim3((unsigned)(c.G * nch)), dim3(64), 0, st, c.S, c.E,
                      c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token, c1,
-                     mean_gate, aux);
+                     mean_gate, aux, static_cast<uint32_t*>(zero_row),
+                     zero_row != nullptr ? c.M / 2 : 0);
   return check_launch();
 }
 

@@ -33,5 +33,9 @@ def test_host_only_entry_points():
     got = moe.moe_workspace_bytes(sh)
     assert need < got < need + (64 << 20)
     assert 0 < moe.moe_gate_workspace_bytes(sh) < got
+    # the paper-size bf16 layer gathers inside the first GEMM; fp32 and short rows do not
+    assert moe.moe_forward_fuses_dispatch(sh) is True
+    assert moe.moe_forward_fuses_dispatch(moe.MoEShape(1, 64, 32, 64, 4, 32, "f32")) is False
+    assert moe.moe_forward_fuses_dispatch(moe.MoEShape(1, 600, 32, 256, 4, 256, "bf16")) is False
     # the workspace of the fp32 layer is twice as wide in its activation buffers
     assert moe.moe_workspace_bytes(moe.MoEShape(1, 64, 32, 64, 4, 32, "f32")) > 128 * (64 + 64) * 4

@@ -46,6 +46,12 @@ SMALL_CASES = [
     MoEConfig("one_k_step", G=1, S=600, M=32, H=256, E=4, C=256, act_dtype="bf16", seed=28),
     MoEConfig("one_k_step_2", G=1, S=600, M=256, H=32, E=4, C=256, act_dtype="bf16", seed=29),
     MoEConfig("many_tiles", G=2, S=1100, M=512, H=768, E=19, C=128, act_dtype="bf16", seed=30),
+    # the layer entry point gathers the rows of the first GEMM straight from x for these
+    # shapes: shortest K the gather takes, a capacity that is no power of two with row tiles
+    # that straddle groups and mostly empty slots; capacity 1; more tiles than compute units
+    MoEConfig("gather_k128", G=16, S=100, M=128, H=256, E=8, C=48, act_dtype="bf16", seed=31),
+    MoEConfig("gather_c1", G=256, S=4, M=160, H=256, E=3, C=1, act_dtype="bf16", seed=32),
+    MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
 ]
 
 
