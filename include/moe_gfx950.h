@@ -165,6 +165,71 @@ int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, co
                        const void* wi, const void* wo, void* y, float* aux,
                        void* ws, size_t ws_bytes, void* stream, void* const* events);
 
+/*
+ * ---- Backward pass -------------------------------------------------------------
+ * The paper trains the layer by differentiating Algorithm 2 automatically; of the
+ * auxiliary loss it states that the counts c_e carry no gradient and the mean gates
+ * m_e do (Section 2.2, "Auxiliary loss").  The entry points below compute that
+ * derivative by the chain rule.  All discrete decisions of Algorithm 1 (top-2 indices,
+ * capacity tests, random routing, c_e) are constants; the normalised weights
+ * g1/(g1+g2), g2/(g1+g2) are differentiated with respect to both raw gates; a choice
+ * that is not kept contributes nothing; relu'(0) = 0.  With
+ *   L = sum dy[g,s,m] y[g,s,m] + sum_g daux[g] l_aux[g]
+ * the outputs are dL/dx, dL/dwg, dL/dwi, dL/dwo.
+ */
+
+/*
+ * moe_forward that also keeps the softmax gates g[G,S,E] (fp32) in the workspace, which
+ * the backward pass reads together with the routing tensors, h and out.  Same arguments,
+ * results and workspace size as moe_forward.
+ */
+int moe_forward_train(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                      const void* wi, const void* wo, void* y, float* aux,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Bytes of workspace moe_backward needs (its own; the forward workspace comes on top).
+ * Pure host function. */
+int moe_backward_workspace_bytes(const moe_config* cfg, size_t* bytes);
+
+/*
+ * Backward of the whole layer (Eq. 1-3 and Algorithms 1-2 differentiated):
+ *   dout[e,g,c,:] = weight[g,s,k] dy[g,s,:],  dweight[g,s,k] = <dy[g,s,:], out[e,g,c,:]>
+ *   dh   = (dout . wo^T) where h > 0          dwo[e] = h[e]^T . dout[e]
+ *   dbuf = dh . wi^T                          dwi[e] = buf[e]^T . dh[e]
+ *   dgate: d(g1/(g1+g2)), d(g2/(g1+g2)) for kept choices, + daux[g] c_e / (E S^2)
+ *   dz   = g (dgate - <g, dgate>)             (softmax)
+ *   dwg  = sum_tokens x^T dz                  dx = sum_k dbuf[e_k,g,c_k,:] + dz . wg^T
+ * in : x, wg, wi, wo as given to the forward call;  dy [G,S,M] act_dtype;
+ *      daux [G] fp32 (gradient of the loss with respect to each group's l_aux);
+ *      fwd_ws: the workspace that a moe_forward_train call with the same cfg, x, wg, u,
+ *      wi, wo has filled (read only here; fwd_ws_bytes >= moe_workspace_bytes)
+ * out: dx [G,S,M] act_dtype;  dwg [M,E] fp32;  dwi [E,M,H], dwo [E,H,M] act_dtype.
+ *      Every output element is written (no accumulation into previous contents).
+ * ws : at least moe_backward_workspace_bytes(cfg), 256-byte aligned, overwritten.
+ * bf16: operands bf16, accumulation fp32, dout / dh / dbuf rounded to bf16 once each;
+ * the gate path (dweight, dz, dwg) is fp32.  Sums over tokens run in a fixed order:
+ * results are reproducible bit for bit.
+ */
+int moe_backward(const moe_config* cfg, const void* x, const float* wg, const void* wi,
+                 const void* wo, const void* dy, const float* daux,
+                 const void* fwd_ws, size_t fwd_ws_bytes,
+                 void* dx, float* dwg, void* dwi, void* dwo,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * moe_backward with stage timing marks (see moe_forward_events): MOE_BACKWARD_EVENTS
+ * caller-owned events recorded on `stream`:
+ *   [0] start  [1] after dout, dweight  [2] after dh  [3] after dwo  [4] after dbuf
+ *   [5] after dwi (includes re-dispatching x)  [6] after dz, dwg  [7] after dx.
+ * events == NULL is exactly moe_backward.
+ */
+#define MOE_BACKWARD_EVENTS 8
+int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, const void* wi,
+                        const void* wo, const void* dy, const float* daux,
+                        const void* fwd_ws, size_t fwd_ws_bytes,
+                        void* dx, float* dwg, void* dwi, void* dwo,
+                        void* ws, size_t ws_bytes, void* stream, void* const* events);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,8 +22,10 @@ SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
            "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
-           "moe_forward_fuses_dispatch")
+           "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
+           "moe_backward", "moe_backward_events")
 FORWARD_EVENTS = 6
+BACKWARD_EVENTS = 8
 
 
 class MoEError(RuntimeError):
@@ -85,6 +87,11 @@ def load_library() -> ctypes.CDLL:
         "moe_forward": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "moe_forward_events": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                ctypes.POINTER(ctypes.c_void_p)],
+        "moe_forward_train": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "moe_backward_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_backward": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp],
+        "moe_backward_events": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp,
+                                                                     ctypes.POINTER(ctypes.c_void_p)],
     }.items():
         fn = getattr(lib, name)
         fn.restype = i32
@@ -225,3 +232,54 @@ def moe_forward_events(shape: MoEShape, x, wg, u, wi, wo, y, aux, ws, events):
         _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
         _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream(), handles),
         "moe_forward_events")
+
+
+def moe_forward_train(shape: MoEShape, x, wg, u, wi, wo, y, aux, ws):
+    """moe_forward that also keeps the softmax gates in ``ws`` for moe_backward."""
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    dt, f32 = shape.torch_dtype, torch.float32
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_forward_train(
+        ctypes.byref(c), _ptr(x, dt, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"),
+        _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
+        _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream()),
+        "moe_forward_train")
+
+
+def moe_backward_workspace_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_backward_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
+           "moe_backward_workspace_bytes")
+    return n.value
+
+
+def _backward_args(shape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws):
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    dt, f32 = shape.torch_dtype, torch.float32
+    fp, fn = _ws(fwd_ws, "fwd_ws")
+    wsp, wsn = _ws(ws)
+    return (_ptr(x, dt, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"), _ptr(wi, dt, (E, M, H), "wi"),
+            _ptr(wo, dt, (E, H, M), "wo"), _ptr(dy, dt, (G, S, M), "dy"), _ptr(daux, f32, (G,), "daux"),
+            fp, fn, _ptr(dx, dt, (G, S, M), "dx"), _ptr(dwg, f32, (M, E), "dwg"),
+            _ptr(dwi, dt, (E, M, H), "dwi"), _ptr(dwo, dt, (E, H, M), "dwo"), wsp, wsn, _stream())
+
+
+def moe_backward(shape: MoEShape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws):
+    """Gradients of the layer; ``fwd_ws`` is the workspace moe_forward_train has filled."""
+    c = shape._c()
+    _check(load_library().moe_backward(
+        ctypes.byref(c), *_backward_args(shape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws)),
+        "moe_backward")
+
+
+def moe_backward_events(shape: MoEShape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws, events):
+    """moe_backward that records BACKWARD_EVENTS torch.cuda.Event objects at its stage boundaries."""
+    if len(events) != BACKWARD_EVENTS:
+        raise ValueError(f"need {BACKWARD_EVENTS} events")
+    handles = (ctypes.c_void_p * BACKWARD_EVENTS)(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    c = shape._c()
+    _check(load_library().moe_backward_events(
+        ctypes.byref(c), *_backward_args(shape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws),
+        handles), "moe_backward_events")

@@ -22,8 +22,8 @@ int check_config(const moe_config* c) {
 
 // Layout of the moe_forward workspace.
 struct ForwardWs {
-  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, buf, h, out, gate_ws,
-      total;
+  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, gates, buf, h, out,
+      gate_ws, total;
 };
 
 ForwardWs carve(const moe_config& c) {
@@ -40,12 +40,87 @@ ForwardWs carve(const moe_config& c) {
   w.c1 = take(GE * 4);
   w.mean_gate = take(GE * 4);
   w.zero_row = take((size_t)c.M * elt);
+  w.gates = take(N * c.E * 4);
   w.buf = take(rows * c.M * elt);
   w.h = take(rows * c.H * elt);
   w.out = take(rows * c.M * elt);
   w.gate_ws = take(moe::gate_workspace_bytes(c));
   w.total = off;
   return w;
+}
+
+// Layout of the moe_backward workspace.
+struct BackwardWs {
+  size_t dout, dh, dbuf, buf, dweight, dz, dwg_partial, total;
+};
+
+BackwardWs carve_bwd(const moe_config& c) {
+  const size_t N = (size_t)c.G * c.S, rows = (size_t)c.E * c.G * c.C;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  BackwardWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.dout = take(rows * c.M * elt);
+  w.dh = take(rows * c.H * elt);
+  w.dbuf = take(rows * c.M * elt);
+  w.buf = take(rows * c.M * elt);
+  w.dweight = take(N * 2 * 4);
+  w.dz = take(N * c.E * 4);
+  w.dwg_partial = take((size_t)moe::dwg_splits(c) * c.M * c.E * 4);
+  w.total = off;
+  return w;
+}
+
+int forward_impl(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                 const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
+                 void* stream, void* const* events, bool keep_gates) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, wg, u, wi, wo, y, aux, ws};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  if (events != nullptr)
+    for (int i = 0; i < MOE_FORWARD_EVENTS; ++i)
+      if (events[i] == nullptr) return MOE_EINVAL;
+  const ForwardWs w = carve(*cfg);
+  if (ws_bytes < w.total) return MOE_EWORKSPACE;
+  char* base = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  auto mark = [&](int i) {
+    return events == nullptr ||
+           hipEventRecord(static_cast<hipEvent_t>(events[i]), st) == hipSuccess;
+  };
+  int32_t* expert_idx = reinterpret_cast<int32_t*>(base + w.expert_idx);
+  int32_t* slot = reinterpret_cast<int32_t*>(base + w.slot);
+  float* weight = reinterpret_cast<float*>(base + w.weight);
+  int32_t* src_token = reinterpret_cast<int32_t*>(base + w.src_token);
+  // bf16 layers whose shape the persistent GEMM takes skip the dispatched buffer: the first
+  // GEMM gathers its rows from x (then the dispatch mark coincides with the gate mark)
+  const bool gather = moe::expert_gemm1_can_gather(*cfg);
+  if (!mark(0)) return MOE_EHIP;
+  rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
+                        reinterpret_cast<int32_t*>(base + w.fill), src_token,
+                        reinterpret_cast<int32_t*>(base + w.c1),
+                        reinterpret_cast<float*>(base + w.mean_gate), aux,
+                        keep_gates ? reinterpret_cast<float*>(base + w.gates) : nullptr,
+                        base + w.gate_ws, gather ? base + w.zero_row : nullptr, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(1)) return MOE_EHIP;
+  if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(2)) return MOE_EHIP;
+  rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
+                                                base + w.h, st)
+              : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(3)) return MOE_EHIP;
+  rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(4)) return MOE_EHIP;
+  rc = moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+  if (rc != MOE_OK) return rc;
+  return mark(5) ? MOE_OK : MOE_EHIP;
 }
 
 }  // namespace
@@ -139,52 +214,88 @@ int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_id
 int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, const float* u,
                        const void* wi, const void* wo, void* y, float* aux, void* ws,
                        size_t ws_bytes, void* stream, void* const* events) {
+  return forward_impl(cfg, x, wg, u, wi, wo, y, aux, ws, ws_bytes, stream, events, false);
+}
+
+int moe_forward_train(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                      const void* wi, const void* wo, void* y, float* aux, void* ws,
+                      size_t ws_bytes, void* stream) {
+  return forward_impl(cfg, x, wg, u, wi, wo, y, aux, ws, ws_bytes, stream, nullptr, true);
+}
+
+int moe_backward_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve_bwd(*cfg).total;
+  return MOE_OK;
+}
+
+int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, const void* wi,
+                        const void* wo, const void* dy, const float* daux, const void* fwd_ws,
+                        size_t fwd_ws_bytes, void* dx, float* dwg, void* dwi, void* dwo, void* ws,
+                        size_t ws_bytes, void* stream, void* const* events) {
   int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
-  const void* req[] = {x, wg, u, wi, wo, y, aux, ws};
+  const void* req[] = {x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
   if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(fwd_ws) & 255u) != 0) return MOE_EINVAL;
   if (events != nullptr)
-    for (int i = 0; i < MOE_FORWARD_EVENTS; ++i)
+    for (int i = 0; i < MOE_BACKWARD_EVENTS; ++i)
       if (events[i] == nullptr) return MOE_EINVAL;
-  const ForwardWs w = carve(*cfg);
-  if (ws_bytes < w.total) return MOE_EWORKSPACE;
+  const ForwardWs f = carve(*cfg);
+  const BackwardWs b = carve_bwd(*cfg);
+  if (fwd_ws_bytes < f.total || ws_bytes < b.total) return MOE_EWORKSPACE;
+  const char* fb = static_cast<const char*>(fwd_ws);
   char* base = static_cast<char*>(ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
   auto mark = [&](int i) {
     return events == nullptr ||
            hipEventRecord(static_cast<hipEvent_t>(events[i]), st) == hipSuccess;
   };
-  int32_t* expert_idx = reinterpret_cast<int32_t*>(base + w.expert_idx);
-  int32_t* slot = reinterpret_cast<int32_t*>(base + w.slot);
-  float* weight = reinterpret_cast<float*>(base + w.weight);
-  int32_t* src_token = reinterpret_cast<int32_t*>(base + w.src_token);
-  // bf16 layers whose shape the persistent GEMM takes skip the dispatched buffer: the first
-  // GEMM gathers its rows from x (then the dispatch mark coincides with the gate mark)
-  const bool gather = moe::expert_gemm1_can_gather(*cfg);
+  const int32_t* expert_idx = reinterpret_cast<const int32_t*>(fb + f.expert_idx);
+  const int32_t* slot = reinterpret_cast<const int32_t*>(fb + f.slot);
+  const float* weight = reinterpret_cast<const float*>(fb + f.weight);
+  const int32_t* src_token = reinterpret_cast<const int32_t*>(fb + f.src_token);
+  float* dweight = reinterpret_cast<float*>(base + b.dweight);
+  float* dz = reinterpret_cast<float*>(base + b.dz);
   if (!mark(0)) return MOE_EHIP;
-  rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
-                        reinterpret_cast<int32_t*>(base + w.fill), src_token,
-                        reinterpret_cast<int32_t*>(base + w.c1),
-                        reinterpret_cast<float*>(base + w.mean_gate), aux, nullptr,
-                        base + w.gate_ws, gather ? base + w.zero_row : nullptr, st);
+  rc = moe::launch_combine_bwd(*cfg, dy, fb + f.out, src_token, expert_idx, weight, base + b.dout,
+                               dweight, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
-  if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
+  rc = moe::launch_expert_dgrad2(*cfg, base + b.dout, wo, fb + f.h, base + b.dh, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
-  rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
-                                                base + w.h, st)
-              : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
+  rc = moe::launch_expert_wgrad2(*cfg, fb + f.h, base + b.dout, dwo, st);
   if (rc != MOE_OK) return rc;
   if (!mark(3)) return MOE_EHIP;
-  rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);
+  rc = moe::launch_expert_dgrad1(*cfg, base + b.dh, wi, base + b.dbuf, st);
   if (rc != MOE_OK) return rc;
   if (!mark(4)) return MOE_EHIP;
-  rc = moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+  rc = moe::launch_dispatch(*cfg, x, src_token, base + b.buf, st);
   if (rc != MOE_OK) return rc;
-  return mark(5) ? MOE_OK : MOE_EHIP;
+  rc = moe::launch_expert_wgrad1(*cfg, base + b.buf, base + b.dh, dwi, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(5)) return MOE_EHIP;
+  rc = moe::launch_gate_bwd(*cfg, x, wg, reinterpret_cast<const float*>(fb + f.gates), expert_idx,
+                            slot, dweight, reinterpret_cast<const int32_t*>(fb + f.c1), daux, dz,
+                            reinterpret_cast<float*>(base + b.dwg_partial), dwg, st);
+  if (rc != MOE_OK) return rc;
+  if (!mark(6)) return MOE_EHIP;
+  rc = moe::launch_dx(*cfg, dz, wg, base + b.dbuf, expert_idx, slot, dx, st);
+  if (rc != MOE_OK) return rc;
+  return mark(7) ? MOE_OK : MOE_EHIP;
+}
+
+int moe_backward(const moe_config* cfg, const void* x, const float* wg, const void* wi,
+                 const void* wo, const void* dy, const float* daux, const void* fwd_ws,
+                 size_t fwd_ws_bytes, void* dx, float* dwg, void* dwi, void* dwo, void* ws,
+                 size_t ws_bytes, void* stream) {
+  return moe_backward_events(cfg, x, wg, wi, wo, dy, daux, fwd_ws, fwd_ws_bytes, dx, dwg, dwi, dwo,
+                             ws, ws_bytes, stream, nullptr);
 }
 
 int moe_forward(const moe_config* cfg, const void* x, const float* wg, const float* u,

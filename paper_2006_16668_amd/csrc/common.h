@@ -45,6 +45,35 @@ template <> struct Elt<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// 16 bytes of a row as floats and back (one rounding on the way back)
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int kElts = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return uint4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                 __float_as_uint(f[3])};
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int kElts = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return uint4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                 pack_bf16x2(f[6], f[7])};
+  }
+};
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -79,6 +108,34 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
 bool expert_gemm1_can_gather(const moe_config& c);
 int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
                                const void* zero_row, const void* wi, void* h, hipStream_t st);
+
+// backward pass (backward.hip); epi of the strided GEMM: 0 none, 1 relu, 2 zero where mask <= 0
+int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
+                       const int32_t* src_token, const int32_t* expert_idx, const float* weight,
+                       void* dout, float* dweight, hipStream_t st);
+int dwg_splits(const moe_config& c);
+int launch_gate_bwd(const moe_config& c, const void* x, const float* wg, const float* gates,
+                    const int32_t* expert_idx, const int32_t* slot, const float* dweight,
+                    const int32_t* c1, const float* daux, float* dz, float* dwg_partial,
+                    float* dwg, hipStream_t st);
+int launch_dx(const moe_config& c, const float* dz, const float* wg, const void* dbuf,
+              const int32_t* expert_idx, const int32_t* slot, void* dx, hipStream_t st);
+int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a_e, long long a_r,
+                        long long a_k, const void* B, long long b_e, long long b_k, long long b_n,
+                        void* Cout, const void* mask, int R, int N, int K, hipStream_t st);
+// expert GEMMs of the backward pass (expert_gemm.hip), per expert with rows = G*C:
+//   dgrad2: dh   = (dout . wo^T) masked by h > 0     [rows,M] x [H,M]^T -> [rows,H]
+//   wgrad2: dwo  = h^T . dout                        [rows,H]^T x [rows,M] -> [H,M]
+//   dgrad1: dbuf = dh . wi^T                         [rows,H] x [M,H]^T -> [rows,M]
+//   wgrad1: dwi  = buf^T . dh                        [rows,M]^T x [rows,H] -> [M,H]
+int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
+                         void* dh, hipStream_t st);
+int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
+                         hipStream_t st);
+int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,
+                         hipStream_t st);
+int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
+                         hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 

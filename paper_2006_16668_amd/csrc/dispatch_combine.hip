@@ -31,34 +31,6 @@ __global__ __launch_bounds__(256) void dispatch_kernel(
   }
 }
 
-template <typename T> struct Vec16;
-template <> struct Vec16<float> {
-  static constexpr int kElts = 4;
-  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
-    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
-    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-  }
-  static __device__ __forceinline__ uint4 pack(const float* f) {
-    return uint4{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
-                 __float_as_uint(f[3])};
-  }
-};
-template <> struct Vec16<bf16_t> {
-  static constexpr int kElts = 8;
-  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(w[i] << 16);
-      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-  }
-  static __device__ __forceinline__ uint4 pack(const float* f) {
-    return uint4{pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
-                 pack_bf16x2(f[6], f[7])};
-  }
-};
-
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(
     const uint4* __restrict__ out, const int32_t* __restrict__ expert_idx,

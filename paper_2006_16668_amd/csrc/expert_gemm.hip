@@ -690,4 +690,33 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
                           static_cast<bf16_t*>(out), c.E, R, c.M, c.H, st);
 }
 
+// ---- backward pass: A K-contiguous x B K-contiguous (dgrad), A and B row(k)-major (wgrad) ----
+int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
+                         void* dh, hipStream_t st) {
+  const long long R = (long long)c.G * c.C;
+  return launch_gemm_strided(c, 2, dout, R * c.M, c.M, 1, wo, (long long)c.H * c.M, 1, c.M, dh, h,
+                             (int)R, c.H, c.M, st);
+}
+
+int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
+                         hipStream_t st) {
+  const long long R = (long long)c.G * c.C;
+  return launch_gemm_strided(c, 0, h, R * c.H, 1, c.H, dout, R * c.M, c.M, 1, dwo, nullptr, c.H,
+                             c.M, (int)R, st);
+}
+
+int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,
+                         hipStream_t st) {
+  const long long R = (long long)c.G * c.C;
+  return launch_gemm_strided(c, 0, dh, R * c.H, c.H, 1, wi, (long long)c.M * c.H, 1, c.H, dbuf,
+                             nullptr, (int)R, c.M, c.H, st);
+}
+
+int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
+                         hipStream_t st) {
+  const long long R = (long long)c.G * c.C;
+  return launch_gemm_strided(c, 0, buf, R * c.M, 1, c.M, dh, R * c.H, c.H, 1, dwi, nullptr, c.M,
+                             c.H, (int)R, st);
+}
+
 }  // namespace moe

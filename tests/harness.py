@@ -56,6 +56,26 @@ def gpu_forward(cfg: MoEConfig, inp):
     return y, aux
 
 
+def gpu_forward_backward(cfg: MoEConfig, inp, dy, daux):
+    """moe_forward_train + moe_backward through the C ABI; returns y, aux and the four gradients."""
+    sh = shape_of(cfg)
+    dev = inp.x.device
+    dt = sh.torch_dtype
+    nan = float("nan")
+    y = torch.full((cfg.G, cfg.S, cfg.M), nan, dtype=dt, device=dev)
+    aux = torch.full((cfg.G,), nan, dtype=torch.float32, device=dev)
+    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_forward_train(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, fws)
+    dx = torch.full((cfg.G, cfg.S, cfg.M), nan, dtype=dt, device=dev)
+    dwg = torch.full((cfg.M, cfg.E), nan, dtype=torch.float32, device=dev)
+    dwi = torch.full((cfg.E, cfg.M, cfg.H), nan, dtype=dt, device=dev)
+    dwo = torch.full((cfg.E, cfg.H, cfg.M), nan, dtype=dt, device=dev)
+    bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_backward(sh, inp.x, inp.wg, inp.wi, inp.wo, dy, daux, fws, dx, dwg, dwi, dwo, bws)
+    torch.cuda.synchronize()
+    return {"y": y, "aux": aux, "dx": dx, "dwg": dwg, "dwi": dwi, "dwo": dwo}
+
+
 def assert_routing_equal(r, want):
     """Integer routing tensors: bit-exact."""
     for k in ("expert_idx", "slot", "fill", "src_token", "c1"):

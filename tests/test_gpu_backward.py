@@ -1,0 +1,107 @@
+"""GPU parity of the backward pass (moe_forward_train + moe_backward through the C ABI)
+against the fp64 backward oracle, element-wise norms on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_16668_amd as moe
+from harness import f64, gpu_forward, gpu_forward_backward, rel_fro, shape_of
+from oracle import moe_oracle_backward as orb
+from test_gpu_parity import SMALL_CASES
+from workloads import ExpertWeightsF64, make_inputs, make_upstream
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# bf16: operands and the three intermediate gradients (dout, dh, dbuf) are rounded to 8
+# mantissa bits once each and accumulated in fp32, so norms agree to a few 2^-9; the gate
+# gradient inherits the rounding of `out` through dweight.  fp32: accumulation order only.
+TOL = {"f32": 2e-5, "bf16": 2e-2}
+
+
+def _oracle(cfg, inp, dy, daux):
+    x, wg, u = inp.host_f64()
+    return orb.moe_backward(x, wg, u, ExpertWeightsF64(inp.wi), ExpertWeightsF64(inp.wo), cfg.C,
+                            f64(dy), f64(daux))
+
+
+def _check(cfg, got, want, tol):
+    assert rel_fro(f64(got["dx"]), want["dx"]) < tol
+    assert rel_fro(f64(got["dwg"]), want["dwg"]) < tol
+    dwi = np.stack([want["dwi"][e] for e in range(cfg.E)])
+    dwo = np.stack([want["dwo"][e] for e in range(cfg.E)])
+    assert rel_fro(f64(got["dwi"]), dwi) < tol
+    assert rel_fro(f64(got["dwo"]), dwo) < tol
+    # per expert too: one broken expert must not hide in the norm over all of them
+    for e in range(cfg.E):
+        if np.linalg.norm(dwi[e]) > 0:
+            assert rel_fro(f64(got["dwi"][e]), dwi[e]) < 2 * tol, e
+            assert rel_fro(f64(got["dwo"][e]), dwo[e]) < 2 * tol, e
+        else:                                            # an expert nobody was routed to
+            assert not f64(got["dwi"][e]).any() and not f64(got["dwo"][e]).any()
+    # per token: rows of dx
+    num = np.linalg.norm(f64(got["dx"]) - want["dx"], axis=-1)
+    den = np.maximum(np.linalg.norm(want["dx"], axis=-1), 1e-30)
+    assert (num / den).max() < 8 * tol
+
+
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_backward_matches_oracle(cfg):
+    print(f"case {cfg}", flush=True)
+    inp = make_inputs(cfg, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    got = gpu_forward_backward(cfg, inp, dy, daux)
+    want = _oracle(cfg, inp, dy, daux)
+    # the training forward is the inference forward
+    y, aux = gpu_forward(cfg, inp)
+    assert torch.equal(got["y"], y) and torch.equal(got["aux"], aux)
+    _check(cfg, got, want, TOL[cfg.act_dtype])
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged_bf16", "gather_k128"])
+def test_auxiliary_loss_gradient_alone(name):
+    """dy = 0: expert-weight gradients vanish exactly, dx and dwg carry only the l_aux term,
+    whose scale c_e/(E S^2) is far below the main term and would hide behind it otherwise."""
+    cfg = next(c for c in SMALL_CASES if c.name == name)
+    inp = make_inputs(cfg, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    dy.zero_()
+    got = gpu_forward_backward(cfg, inp, dy, daux)
+    want = _oracle(cfg, inp, dy, daux)
+    assert not f64(got["dwi"]).any() and not f64(got["dwo"]).any()
+    assert rel_fro(f64(got["dwg"]), want["dwg"]) < 1e-4
+    assert rel_fro(f64(got["dx"]), want["dx"]) < (1e-4 if cfg.act_dtype == "f32" else 1e-2)
+
+
+def test_backward_is_deterministic_and_linear():
+    cfg = next(c for c in SMALL_CASES if c.name == "small")
+    inp = make_inputs(cfg, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    a = gpu_forward_backward(cfg, inp, dy, daux)
+    b = gpu_forward_backward(cfg, inp, dy, daux)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    # scaling the upstream gradients by a power of two scales every gradient exactly
+    c = gpu_forward_backward(cfg, inp, dy * 2, daux * 2)
+    for k in ("dx", "dwg", "dwi", "dwo"):
+        assert torch.equal(c[k], a[k] * 2), k
+
+
+def test_backward_argument_errors():
+    sh = moe.MoEShape(1, 64, 32, 64, 4, 32, "f32")
+    cfg = next(c for c in SMALL_CASES if c.name == "tiny")
+    inp = make_inputs(cfg, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    f32 = dict(dtype=torch.float32, device=DEV)
+    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    dx, dwg = torch.empty((1, 64, 32), **f32), torch.empty((32, 4), **f32)
+    dwi, dwo = torch.empty((4, 32, 64), **f32), torch.empty((4, 64, 32), **f32)
+    with pytest.raises(moe.MoEError) as ei:           # backward workspace too small
+        moe.moe_backward(sh, inp.x, inp.wg, inp.wi, inp.wo, dy, daux, fws, dx, dwg, dwi, dwo, bws[:-256])
+    assert ei.value.status == -3
+    with pytest.raises(moe.MoEError) as ei:           # forward workspace too small
+        moe.moe_backward(sh, inp.x, inp.wg, inp.wi, inp.wo, dy, daux, fws[:-256], dx, dwg, dwi, dwo, bws)
+    assert ei.value.status == -3
+    with pytest.raises(ValueError):
+        moe.moe_backward(sh, inp.x, inp.wg, inp.wi, inp.wo, dy[:, :32], daux, fws, dx, dwg, dwi, dwo, bws)

@@ -1,10 +1,10 @@
-"""Seeded synthetic inputs for the MoE-layer forward pass.
+"""Seeded synthetic inputs for the MoE layer (forward inputs and upstream gradients).
 
 This module serves the HIP library's tests, the benchmark and the CPU oracle's
 tests alike.  It holds none of the layer's arithmetic and imports neither side.
 """
 from .configs import CONFIGS, MoEConfig, get_config
-from .generate import MoEInputs, make_inputs, ExpertWeightsF64
+from .generate import MoEInputs, make_inputs, make_upstream, ExpertWeightsF64
 
-__all__ = ["CONFIGS", "MoEConfig", "get_config", "MoEInputs", "make_inputs",
+__all__ = ["CONFIGS", "MoEConfig", "get_config", "MoEInputs", "make_inputs", "make_upstream",
            "ExpertWeightsF64"]

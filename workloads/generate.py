@@ -152,3 +152,14 @@ def make_inputs(cfg: MoEConfig, device="cpu", margin=1e-3, u_margin=1e-4,
 
     return MoEInputs(cfg, x.view(G, S, M), wg, u.view(G, S), wi, wo,
                      redrawn_rows, redrawn_u)
+
+
+def make_upstream(cfg: MoEConfig, device="cpu"):
+    """Upstream gradients for the backward pass: dy [G,S,M] ~ N(0,1) rounded to the
+    activation type, daux [G] ~ N(0,1) fp32 (a generator of their own, seeded from cfg.seed)."""
+    device = torch.device(device)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed + 104729)
+    dy = _randn((cfg.G, cfg.S, cfg.M), gen, device).to(_TORCH_DTYPE[cfg.act_dtype])
+    daux = _randn((cfg.G,), gen, device)
+    return dy, daux
