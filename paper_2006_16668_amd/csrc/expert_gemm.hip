@@ -246,12 +246,24 @@ struct DmaSmem {
 // GATHER: the A rows are not a dense [E,R,K] buffer but rows of x picked by the dispatch
 // indices (A = x [G,S,K]; row r of expert e is x[r / C, src_token[e,r], :], a zero row when
 // the slot is empty), i.e. the dispatch of Algorithm 2 folded into the first GEMM's copies.
-template <int ST, bool RELU, bool GATHER>
+//
+// Operand layouts.  "K-contiguous" (KC): the operand is stored [rows][K] (row = its index in
+// the output) and staged as [256 rows][4 chunks]; "row-of-k" (MNC): stored [K][rows] and
+// staged as [32 k][32 chunks], read with the transposing LDS load.  Either operand can have
+// either layout; both fragment kinds hand a lane the 8 consecutive k of its row:
+//   forward       C = A . B        A KC  [R,K],  B MNC [K,N]
+//   data gradient C = A . B^T      A KC  [R,K],  B KC  [N,K]      (A_MNC = false, B_KC = true)
+//   weight grad.  C = A^T . B      A MNC [K,R],  B MNC [K,N]      (A_MNC = true,  B_KC = false)
+// EPI: 0 plain, 1 relu, 2 zero every element whose `mask` element (same [E,R,N] index as C)
+// is zero -- the derivative of relu taken from the stored activations.
+template <int ST, int EPI, bool GATHER, bool A_MNC, bool B_KC>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
     int R, int N, int K, int tiles_m, int tiles_n, int ntiles,
     const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
-    uint32_t c_magic, int c_shift) {
+    uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask) {
+  static_assert(!(GATHER && A_MNC), "the gather form addresses whole rows of a K-contiguous A");
+  constexpr bool RELU = EPI == 1;
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -284,10 +296,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   for (int q = 0; q < 4; ++q) {
     const int row = 16 * (wave * 4 + q) + (lane >> 2);
     const int ca = (lane & 3) ^ ((row >> 2) & 3);
-    a_voff[q] = (uint32_t)((row * K + 8 * ca) * 2);
     const int krow = 2 * (wave * 4 + q) + (lane >> 5);
     const int cb = (lane & 31) ^ (4 * (krow & 3));
-    b_voff[q] = (uint32_t)((krow * N + 8 * cb) * 2);
+    a_voff[q] = A_MNC ? (uint32_t)((krow * R + 8 * cb) * 2) : (uint32_t)((row * K + 8 * ca) * 2);
+    b_voff[q] = B_KC ? (uint32_t)((row * K + 8 * ca) * 2) : (uint32_t)((krow * N + 8 * cb) * 2);
   }
 
   // producer cursor: the next step to copy (tile p_tile, k step p_kt) and its sources
@@ -331,8 +343,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   {                                                                                          \
     const int e_ = p_tile / per_e, t_ = p_tile - e_ * per_e;                                 \
     if (GATHER) MOE_DMA_GATHER_ROWS(e_, (t_ % tiles_m) * BM)                                 \
+    else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)(t_ % tiles_m) * BM;              \
     else p_a = A + ((size_t)e_ * R + (size_t)(t_ % tiles_m) * BM) * K;                       \
-    p_b = B + (size_t)e_ * K * N + (size_t)(t_ / tiles_m) * BN;                              \
+    if (B_KC) p_b = B + ((size_t)e_ * N + (size_t)(t_ / tiles_m) * BN) * K;                  \
+    else p_b = B + (size_t)e_ * K * N + (size_t)(t_ / tiles_m) * BN;                         \
   }
 #define MOE_DMA_ADVANCE()                                                                    \
   {                                                                                          \
@@ -341,8 +355,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     if (GATHER) {                                                                            \
       _Pragma("unroll") for (int q = 0; q < 4; ++q) a_addr[q] += BK * 2;                     \
       if (p_kt == KT - 4 && p_tile + stride < t_end) MOE_DMA_TOKENS(p_tile + stride)         \
-    } else p_a += BK;                                                                        \
-    p_b += (size_t)BK * N;                                                                   \
+    } else p_a += A_MNC ? (size_t)BK * R : (size_t)BK;                                       \
+    p_b += B_KC ? (size_t)BK : (size_t)BK * N;                                               \
     if (++p_kt == KT) { p_kt = 0; p_tile += stride; if (p_g < G) MOE_DMA_SET_SOURCES() }     \
   }
   if (GATHER) {
@@ -351,38 +365,42 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   }
   MOE_DMA_SET_SOURCES()
 
-  // fragment read offsets (bytes inside a stage)
-  //   A: row wm0 + 32 i + lane%32, chunk 2 kk + lane/32 at its permuted position
+  // fragment read offsets (bytes inside a stage); w0 = the wavefront's first row of the operand
+  //   KC operand: row w0 + 32 i + lane%32, chunk 2 kk + lane/32 at its permuted position
+  //   MNC operand (transposing read): 16-lane block b = lane/16 covers k rows
+  //   8 (b/2) + (lane%16)/4 (+4), rows w0 + 32 j + 16 (b%2) + 4 (lane%4) .. +3; chunk = row / 8
   const int ar = lane & 31;
-  uint32_t a_rd[2];
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk)
-    a_rd[kk] = (uint32_t)((wm0 + ar) * 64 + (((2 * kk + (lane >> 5)) ^ ((ar >> 2) & 3)) * 16));
-  //   B (transposing read): 16-lane block b = lane/16 covers k rows 8 (b/2) + (lane%16)/4 (+4),
-  //   columns wn0 + 32 j + 16 (b%2) + 4 (lane%4) .. +3; chunk = column / 8
   const int p16 = lane & 15, bb = lane >> 4;
   const int bk = 8 * (bb >> 1) + (p16 >> 2);                   // k row inside a 16-wide step
   const int bsw = 4 * (bk & 3);                                // permutation of that row
-  uint32_t b_rd[TN];
+  uint32_t a_rd[4], b_rd[4];                                   // KC: [kk], MNC: [sub-tile]
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int c = (wn0 >> 3) + 4 * j + 2 * (bb & 1) + ((p16 & 3) >> 1);
-    b_rd[j] = (uint32_t)(SM::kAStage + bk * 512 + ((c ^ bsw) * 16) + (p16 & 1) * 8);
+  for (int j = 0; j < 4; ++j) {
+    const int kc_chunk = (2 * (j & 1) + (lane >> 5)) ^ ((ar >> 2) & 3);
+    const int ca = (wm0 >> 3) + 4 * j + 2 * (bb & 1) + ((p16 & 3) >> 1);
+    const int cb = (wn0 >> 3) + 4 * j + 2 * (bb & 1) + ((p16 & 3) >> 1);
+    a_rd[j] = A_MNC ? (uint32_t)(bk * 512 + ((ca ^ bsw) * 16) + (p16 & 1) * 8)
+                    : (uint32_t)((wm0 + ar) * 64 + kc_chunk * 16);
+    b_rd[j] = B_KC ? (uint32_t)(SM::kAStage + (wn0 + ar) * 64 + kc_chunk * 16)
+                   : (uint32_t)(SM::kAStage + bk * 512 + ((cb ^ bsw) * 16) + (p16 & 1) * 8);
   }
   typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
   typedef bf16x8_t __attribute__((address_space(3))) * lds_bf16x8_ptr;
   struct Frags { bf16x8_t a[TM]; bf16x8_t b[TN]; };
-#define MOE_DMA_READ_A(F, STAGE, kk, i)                                                      \
-  (F).a[i] = *(lds_bf16x8_ptr)(uintptr_t)(lds0 + (STAGE) * SM::kStage + a_rd[kk] + (i) * 32 * 64);
-#define MOE_DMA_READ_B(F, STAGE, kk, j)                                                      \
+#define MOE_DMA_READ_KC(DST, STAGE, RD, kk, i)                                               \
+  DST = *(lds_bf16x8_ptr)(uintptr_t)(lds0 + (STAGE) * SM::kStage + RD[kk] + (i) * 32 * 64);
+#define MOE_DMA_READ_MNC(DST, STAGE, RD, kk, j)                                              \
   {                                                                                          \
-    const uint32_t pb_ = lds0 + (STAGE) * SM::kStage + b_rd[j] + (kk) * 16 * 512;            \
+    const uint32_t pb_ = lds0 + (STAGE) * SM::kStage + RD[j] + (kk) * 16 * 512;              \
     const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pb_); \
     const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                              \
         (lds_s16x4_ptr)(uintptr_t)(pb_ + 4 * 512));                                          \
-    (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                  \
-                                  __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));  \
+    DST = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
   }
+#define MOE_DMA_READ_A(F, STAGE, kk, i)                                                      \
+  { if (A_MNC) MOE_DMA_READ_MNC((F).a[i], STAGE, a_rd, kk, i) else { MOE_DMA_READ_KC((F).a[i], STAGE, a_rd, kk, i) } }
+#define MOE_DMA_READ_B(F, STAGE, kk, j)                                                      \
+  { if (B_KC) { MOE_DMA_READ_KC((F).b[j], STAGE, b_rd, kk, j) } else MOE_DMA_READ_MNC((F).b[j], STAGE, b_rd, kk, j) }
   // The weight fragment goes in as the first MFMA operand: the 32x32 result is then
   // the transposed tile, i.e. a lane owns 4 consecutive columns of one row of C.
 #define MOE_DMA_MFMA_ROW(F, i)                                                               \
@@ -468,7 +486,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
     const int e = c_tile / per_e, t = c_tile - e * per_e;
     const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
-    bf16_t* Ce = Cout + ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
+    const size_t c_off = ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
+    bf16_t* Ce = Cout + c_off;
     const uint32_t st_base = lds0 + (stage == 0 ? ST - 1 : stage - 1) * SM::kStage + wave * 8192;
     const int r32 = lane & 31, hh = lane >> 5;
     const uint32_t st_wr = st_base + r32 * 256 + 8 * (hh ^ (r32 >> 4));
@@ -476,6 +495,13 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     typedef u32x4_t __attribute__((address_space(3))) * lds_u4_ptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+      u32x4_t mk[8];
+      if (EPI == 2) {
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps)
+          mk[ps] = *reinterpret_cast<const u32x4_t*>(
+              mask + c_off + (size_t)(32 * i + 4 * ps + (lane >> 4)) * N + 8 * (lane & 15));
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -490,6 +516,11 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
         const int rr = 4 * ps + (lane >> 4), c = lane & 15;
         u32x4_t d = *(lds_u4_ptr)(uintptr_t)(st_base + rr * 256 + ((c ^ (rr & 15)) * 16));
         if (ps >= 4) d = u32x4_t{d[2], d[3], d[0], d[1]};      // rows 16..31: halves were swapped
+        if (EPI == 2) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            d[w] &= ((mk[ps][w] & 0xffffu) ? 0xffffu : 0u) | ((mk[ps][w] >> 16) ? 0xffff0000u : 0u);
+        }
         *reinterpret_cast<u32x4_t*>(Ce + (size_t)(32 * i + rr) * N + 8 * c) = d;
       }
       __builtin_amdgcn_sched_barrier(0);   // one row group at a time: small register need
@@ -502,13 +533,16 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #undef MOE_DMA_COPY_A
 #undef MOE_DMA_ADVANCE
 #undef MOE_DMA_READ_A
+#undef MOE_DMA_READ_KC
+#undef MOE_DMA_READ_MNC
 #undef MOE_DMA_READ_B
 #undef MOE_DMA_MFMA_ROW
 }
 
-template <int ST, bool RELU, bool GATHER>
+template <int ST, int EPI, bool GATHER, bool A_MNC = false, bool B_KC = false>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
-                    const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st) {
+                    const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st,
+                    const bf16_t* mask = nullptr) {
   using SM = DmaSmem<ST>;
   constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0);
   // n / C for n < 2^31 as (n * c_magic) >> (32 + c_shift), c_magic = ceil(2^(31+l) / C) with
@@ -521,7 +555,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
     c_magic = (uint32_t)((((unsigned long long)1 << (31 + l)) + C - 1) / C);
     c_shift = l - 1;
   }
-  auto kern = expert_gemm_bf16_dma_kernel<ST, RELU, GATHER>;
+  auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC>;
   static bool attr_set = false;   // idempotent: a repeated call sets the same value
   static int cus = 0;
   if (!attr_set) {
@@ -539,14 +573,14 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
-                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift);
+                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask);
   return check_launch();
 }
 
 // shapes the persistent 256x256 kernel takes (its per-lane byte offsets are 32-bit)
 inline bool dma_shape_ok(int R, int N, int K) {
-  return R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && (long long)256 * K * 2 < (1LL << 31) &&
-         (long long)32 * N * 2 < (1LL << 31);
+  const long long big = R > N ? (R > K ? R : K) : (N > K ? N : K);
+  return R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && 256 * big * 2 < (1LL << 31);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
@@ -581,7 +615,8 @@ template <bool RELU>
 int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
               hipStream_t st) {
   if (dma_shape_ok(R, N, K))
-    return launch_bf16_dma<4, RELU, false>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0, st);
+    return launch_bf16_dma<4, RELU ? 1 : 0, false>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0,
+                                                   st);
   if (R > 128 && N >= 256) return launch_bf16<256, 256, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
   return launch_bf16<128, 128, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
 }
@@ -673,7 +708,7 @@ bool expert_gemm1_can_gather(const moe_config& c) {
 int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
                                const void* zero_row, const void* wi, void* h, hipStream_t st) {
   if (!expert_gemm1_can_gather(c)) return MOE_EUNSUPPORTED;
-  return launch_bf16_dma<4, true, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
+  return launch_bf16_dma<4, 1, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
                                         static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
                                         static_cast<const bf16_t*>(zero_row), c.S, c.C, st);
 }
@@ -694,6 +729,10 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
 int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
                          void* dh, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.H, c.M))
+    return launch_bf16_dma<4, 2, false, false, true>(
+        static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
+        c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, static_cast<const bf16_t*>(h));
   return launch_gemm_strided(c, 2, dout, R * c.M, c.M, 1, wo, (long long)c.H * c.M, 1, c.M, dh, h,
                              (int)R, c.H, c.M, st);
 }
@@ -701,6 +740,10 @@ int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, 
 int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.H, c.M, (int)R))
+    return launch_bf16_dma<4, 0, false, true, false>(
+        static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dwo),
+        c.E, c.H, c.M, (int)R, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, h, R * c.H, 1, c.H, dout, R * c.M, c.M, 1, dwo, nullptr, c.H,
                              c.M, (int)R, st);
 }
@@ -708,6 +751,10 @@ int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, v
 int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.M, c.H))
+    return launch_bf16_dma<4, 0, false, false, true>(
+        static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(dbuf),
+        c.E, (int)R, c.M, c.H, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, dh, R * c.H, c.H, 1, wi, (long long)c.M * c.H, 1, c.H, dbuf,
                              nullptr, (int)R, c.M, c.H, st);
 }
@@ -715,6 +762,10 @@ int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, vo
 int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.M, c.H, (int)R))
+    return launch_bf16_dma<4, 0, false, true, false>(
+        static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dwi),
+        c.E, c.M, c.H, (int)R, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, buf, R * c.M, 1, c.M, dh, R * c.H, c.H, 1, dwi, nullptr, c.M,
                              c.H, (int)R, st);
 }
