@@ -61,6 +61,42 @@ def cpu_baseline(cfg, inp, seconds_hint=20.0):
                       f"fp64 numpy, {t_total:.1f} s; includes widening each expert's weights to fp64"}
 
 
+def time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak):
+    """Backward pass of the same layer (not part of `value`): K calls of moe_backward_events
+    after one moe_forward_train, stage times from HIP events on the kernels' stream."""
+    import torch
+    from workloads import make_upstream
+    dev = inp.x.device
+    dy, daux = make_upstream(cfg, device=dev)
+    dx = torch.empty_like(inp.x)
+    dwg = torch.empty_like(inp.wg)
+    dwi, dwo = torch.empty_like(inp.wi), torch.empty_like(inp.wo)
+    bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_forward_train(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+    n_ev = moe.binding.BACKWARD_EVENTS
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(K)]
+    for evs in events:
+        for e in evs:
+            e.record()
+    args = (sh, inp.x, inp.wg, inp.wi, inp.wo, dy, daux, ws, dx, dwg, dwi, dwo, bws)
+    for _ in range(W):
+        moe.moe_backward(*args)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        moe.moe_backward_events(*args, events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    names = ["combine_bwd", "dgrad2_dh", "wgrad2_dwo", "dgrad1_dbuf", "wgrad1_dwi", "gate_bwd_dwg", "dx"]
+    stage_ms = {n: sum(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K)) / K
+                for i, n in enumerate(names)}
+    gemm_ms = sum(stage_ms[n] for n in names[1:5])
+    flops = 4 * 2.0 * cfg.M * cfg.H * kept_rows          # four GEMMs over the kept rows
+    return {"ms_per_step": (t1 - t0) * 1e3 / K, "stages_ms": stage_ms,
+            "gemm_mfma_frac": flops / (gemm_ms * 1e-3) / 1e12 / peak,
+            "note": "moe_backward after moe_forward_train on the same inputs; not part of value"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +104,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip the extra (untimed for the metric) measurement of the backward pass")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (yardstick for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters); not part of the timed region")
@@ -162,6 +200,8 @@ def main():
         "ffn_mfma_frac": 2 * flops_launch / ((stage_ms["expert_gemm1"] + stage_ms["expert_gemm2"]) * 1e-3)
                          / 1e12 / peak,
     }
+    if not args.no_backward:
+        out["backward"] = time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(out))

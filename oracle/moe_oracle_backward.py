@@ -152,10 +152,18 @@ def moe_backward(x, wg, u, wi, wo, C, dy, daux, experts=None):
     dout, dweight = combine_backward(routing, out, dy)
     dbuf = np.zeros_like(buf)
     dwi, dwo = {}, {}
+    src = routing["src_token"]
     for e in range(E):
-        rows = buf[e].reshape(G * C, M)
-        drows, dwi_e, dwo_e = expert_ffn_backward(rows, wi[e], wo[e], dout[e].reshape(G * C, M))
-        dbuf[e] = drows.reshape(G, C, M)
+        # occupied slots only: an empty slot holds a zero row and a zero gradient, which
+        # contribute nothing to either weight gradient
+        gi, ci = np.nonzero(src[e] >= 0)
+        if gi.size == 0:
+            if e in want:
+                dwi[e] = np.zeros(np.shape(wi[e]))
+                dwo[e] = np.zeros(np.shape(wo[e]))
+            continue
+        drows, dwi_e, dwo_e = expert_ffn_backward(buf[e, gi, ci], wi[e], wo[e], dout[e, gi, ci])
+        dbuf[e, gi, ci] = drows
         if e in want:
             dwi[e], dwo[e] = dwi_e, dwo_e
     dx = dispatch_backward(routing, dbuf, x.shape)
@@ -163,8 +171,9 @@ def moe_backward(x, wg, u, wi, wo, C, dy, daux, experts=None):
     dgates = gating_backward(routing["gates"], routing, dweight, daux)
     dlogits = softmax_backward(routing["gates"], dgates)
     # logits[g,s,e] = sum_m x[g,s,m] wg[m,e]
-    dwg = np.einsum("gsm,gse->me", x, dlogits)
-    dx = dx + np.einsum("gse,me->gsm", dlogits, wg)
+    E_ = dlogits.shape[-1]
+    dwg = x.reshape(-1, M).T @ dlogits.reshape(-1, E_)
+    dx = dx + (dlogits.reshape(-1, E_) @ wg.T).reshape(G, S, M)
     return {"dx": dx, "dwg": dwg, "dwi": dwi, "dwo": dwo, "dout": dout, "dbuf": dbuf,
             "dweight": dweight, "dgates": dgates, "dlogits": dlogits, "routing": routing,
             "y": y, "buf": buf, "out": out}

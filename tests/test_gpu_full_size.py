@@ -83,3 +83,42 @@ def test_full_size_forward(name):
         out_want = orc.expert_ffn(rows.reshape(-1, cfg.M), wi[e], wo[e]).reshape(cfg.G, cfg.C, cfg.M)
         assert rel_fro(f64(out[e]), out_want) < 2e-2, f"out[{e}]"
     print("sampled experts done", flush=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["paper", "skewed", "many_experts"])
+def test_full_size_backward(name):
+    """moe_forward_train + moe_backward at the benchmarked sizes against the whole fp64
+    backward oracle: dx and dwg on everything, dwi / dwo on sampled experts (widening every
+    expert's gradient to fp64 on the host would only add copies)."""
+    import time
+    from harness import gpu_forward_backward
+    from oracle import moe_oracle_backward as orb
+    from workloads import make_upstream
+    cfg = CONFIGS[name]
+    print(f"case {cfg}", flush=True)
+    inp = make_inputs(cfg, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    got = gpu_forward_backward(cfg, inp, dy, daux)
+    for k in ("dx", "dwg", "dwi", "dwo"):
+        assert torch.isfinite(got[k].float()).all(), k
+    print("gpu backward done", flush=True)
+    rng = np.random.default_rng(cfg.seed + 1)
+    experts = sorted(set(int(e) for e in rng.integers(0, cfg.E, 4)))
+    x, wg, u = inp.host_f64()
+    t0 = time.perf_counter()
+    want = orb.moe_backward(x, wg, u, ExpertWeightsF64(inp.wi), ExpertWeightsF64(inp.wo), cfg.C,
+                            f64(dy), f64(daux), experts=experts)
+    print(f"oracle backward done in {time.perf_counter() - t0:.0f} s", flush=True)
+    tol = 2e-2
+    assert rel_fro(f64(got["dx"]), want["dx"]) < tol
+    assert rel_fro(f64(got["dwg"]), want["dwg"]) < tol
+    num = np.linalg.norm(f64(got["dx"]) - want["dx"], axis=-1)
+    den = np.maximum(np.linalg.norm(want["dx"], axis=-1), 1e-30)
+    assert (num / den).max() < 8 * tol
+    for e in experts:
+        assert rel_fro(f64(got["dwi"][e]), want["dwi"][e]) < tol, e
+        assert rel_fro(f64(got["dwo"][e]), want["dwo"][e]) < tol, e
+    # softmax gradients sum to zero over the experts of a token, hence so do the rows of dwg
+    dwg = f64(got["dwg"])
+    assert np.abs(dwg.sum(axis=1)).max() < 1e-4 * np.abs(dwg).sum(axis=1).max()
