@@ -51,7 +51,7 @@ ForwardWs carve(const moe_config& c) {
 
 // Layout of the moe_backward workspace.
 struct BackwardWs {
-  size_t dout, dh, dbuf, buf, dweight, dz, dwg_partial, total;
+  size_t dout, dh, dbuf, buf, dweight, dz, dzp, wgp, dxg, dwg_partial, total;
 };
 
 BackwardWs carve_bwd(const moe_config& c) {
@@ -65,8 +65,12 @@ BackwardWs carve_bwd(const moe_config& c) {
   w.dbuf = take(rows * c.M * elt);
   w.buf = take(rows * c.M * elt);
   w.dweight = take(N * 2 * 4);
-  w.dz = take(N * c.E * 4);
-  w.dwg_partial = take((size_t)moe::dwg_splits(c) * c.M * c.E * 4);
+  const moe::GateBwdPlan p = moe::gate_bwd_plan(c);
+  w.dz = take(p.dz_bytes);
+  w.dzp = take(p.dzp_bytes);
+  w.wgp = take(p.wgp_bytes);
+  w.dxg = take(p.dxg_bytes);
+  w.dwg_partial = take(p.partial_bytes);
   w.total = off;
   return w;
 }
@@ -260,7 +264,11 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
   const float* weight = reinterpret_cast<const float*>(fb + f.weight);
   const int32_t* src_token = reinterpret_cast<const int32_t*>(fb + f.src_token);
   float* dweight = reinterpret_cast<float*>(base + b.dweight);
-  float* dz = reinterpret_cast<float*>(base + b.dz);
+  const moe::GateBwdWs gw{reinterpret_cast<float*>(base + b.dz),
+                          reinterpret_cast<moe::bf16_t*>(base + b.dzp),
+                          reinterpret_cast<moe::bf16_t*>(base + b.wgp),
+                          reinterpret_cast<float*>(base + b.dxg),
+                          reinterpret_cast<float*>(base + b.dwg_partial)};
   if (!mark(0)) return MOE_EHIP;
   rc = moe::launch_combine_bwd(*cfg, dy, fb + f.out, src_token, expert_idx, weight, base + b.dout,
                                dweight, st);
@@ -281,11 +289,11 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
   if (rc != MOE_OK) return rc;
   if (!mark(5)) return MOE_EHIP;
   rc = moe::launch_gate_bwd(*cfg, x, wg, reinterpret_cast<const float*>(fb + f.gates), expert_idx,
-                            slot, dweight, reinterpret_cast<const int32_t*>(fb + f.c1), daux, dz,
-                            reinterpret_cast<float*>(base + b.dwg_partial), dwg, st);
+                            slot, dweight, reinterpret_cast<const int32_t*>(fb + f.c1), daux, gw,
+                            dwg, st);
   if (rc != MOE_OK) return rc;
   if (!mark(6)) return MOE_EHIP;
-  rc = moe::launch_dx(*cfg, dz, wg, base + b.dbuf, expert_idx, slot, dx, st);
+  rc = moe::launch_dx(*cfg, wg, base + b.dbuf, expert_idx, slot, gw, dx, st);
   if (rc != MOE_OK) return rc;
   return mark(7) ? MOE_OK : MOE_EHIP;
 }

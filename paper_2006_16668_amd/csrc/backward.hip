@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
     const float* __restrict__ gates, const int32_t* __restrict__ expert_idx,
     const int32_t* __restrict__ slot, const float* __restrict__ dweight,
     const int32_t* __restrict__ c1, const float* __restrict__ daux, float* __restrict__ dz,
-    int S, int E, long long tokens) {
+    bf16_t* __restrict__ dzp, int cols, int S, int E, long long tokens) {
   const long long n = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (n >= tokens) return;
   const int lane = threadIdx.x & 63;
@@ -91,7 +91,60 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(
   dot = wave_sum(dot);
   for (int e = lane; e < E; e += 64) {
     const float dp = scale * (float)cg[e] + (e == e1 ? t1 : 0.f) + (e == e2 ? t2 : 0.f);
-    dz[n * E + e] = p[e] * (dp - dot);
+    const float v = p[e] * (dp - dot);
+    if (dz != nullptr) dz[n * E + e] = v;
+    if (dzp != nullptr) {
+      // v = hi + mid + lo exactly (three bf16 terms cover the 24 mantissa bits), stored side
+      // by side so that a bf16 matrix product over these columns is an fp32-faithful one
+      const bf16_t hi = f32_to_bf16(v);
+      const float r1 = v - bf16_to_f32(hi);
+      const bf16_t mid = f32_to_bf16(r1);
+      const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+      bf16_t* d = dzp + n * cols + 3 * e;
+      d[0] = hi; d[1] = mid; d[2] = lo;
+    }
+  }
+  if (dzp != nullptr)
+    for (int cidx = 3 * E + lane; cidx < cols; cidx += 64) dzp[n * cols + cidx] = 0;
+}
+
+// wgp[m, 3e+p] = bf16(wg[m,e]) for the three terms p of dz, zero in the padding columns
+__global__ __launch_bounds__(256) void wg_pack_bwd_kernel(
+    const float* __restrict__ wg, bf16_t* __restrict__ wgp, int M, int E, int cols) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)M * cols) return;
+  const int m = (int)(i / cols), cidx = (int)(i % cols);
+  wgp[i] = cidx < 3 * E ? f32_to_bf16(wg[(size_t)m * E + cidx / 3]) : (bf16_t)0;
+}
+
+// dx[n,:] = round( dxg[n,:] + dbuf row of the first kept choice + of the second ), bf16
+__global__ __launch_bounds__(256) void dx_rows_kernel(
+    const float4* __restrict__ dxg, const uint4* __restrict__ dbuf,
+    const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ slot,
+    uint4* __restrict__ dx, int S, int G, int C, int vec_per_row, long long tokens) {
+  const long long n = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (n >= tokens) return;
+  const int lane = threadIdx.x & 63;
+  const int g = (int)(n / S);
+  const int s0 = slot[2 * n], s1 = slot[2 * n + 1];
+  const uint4* r0 = s0 >= 0 ? dbuf + (((long long)expert_idx[2 * n] * G + g) * C + s0) * vec_per_row : nullptr;
+  const uint4* r1 = s1 >= 0 ? dbuf + (((long long)expert_idx[2 * n + 1] * G + g) * C + s1) * vec_per_row : nullptr;
+  for (int v = lane; v < vec_per_row; v += 64) {
+    const float4 a = dxg[(n * vec_per_row + v) * 2], b = dxg[(n * vec_per_row + v) * 2 + 1];
+    float acc[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    if (r0 != nullptr) {
+      float f[8];
+      Vec16<bf16_t>::unpack(r0[v], f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += f[i];
+    }
+    if (r1 != nullptr) {
+      float f[8];
+      Vec16<bf16_t>::unpack(r1[v], f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += f[i];
+    }
+    dx[n * vec_per_row + v] = Vec16<bf16_t>::pack(acc);
   }
 }
 
@@ -140,12 +193,20 @@ __global__ __launch_bounds__(256) void dwg_partial_kernel(
     }
 }
 
+// dwg[m,e] = sum over token ranges (in order) of the `terms` adjacent columns of e
 __global__ __launch_bounds__(256) void dwg_reduce_kernel(
-    const float* __restrict__ partial, float* __restrict__ dwg, long long size, int splits) {
+    const float* __restrict__ partial, float* __restrict__ dwg, int M, int E, int cols, int terms,
+    int splits) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= size) return;
+  if (i >= (long long)M * E) return;
+  const int m = (int)(i / E), e = (int)(i % E);
   float acc = 0.f;
-  for (int s = 0; s < splits; ++s) acc += partial[(size_t)s * size + i];
+  for (int s = 0; s < splits; ++s) {
+    const float* p = partial + ((size_t)s * M + m) * cols + (size_t)terms * e;
+    float t = p[0];
+    for (int k = 1; k < terms; ++k) t += p[k];
+    acc += t;
+  }
   dwg[i] = acc;
 }
 
@@ -312,49 +373,99 @@ int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
   return check_launch();
 }
 
-int dwg_splits(const moe_config& c) {
+GateBwdPlan gate_bwd_plan(const moe_config& c) {
+  GateBwdPlan p{};
   const long long tokens = (long long)c.G * c.S;
-  const long long s = (tokens + 511) / 512;
-  return (int)(s < 1 ? 1 : (s > 128 ? 128 : s));
+  const long long cols = ((long long)3 * c.E + 255) / 256 * 256;
+  p.mfma = c.act_dtype == MOE_BF16 && tokens % 256 == 0 && tokens <= 0x7fffffffLL &&
+           cols <= 0x7fffffffLL && gemm_bf16_f32out_ok((int)tokens, c.M, (int)cols) &&
+           gemm_bf16_f32out_ok(c.M, (int)cols, 128);
+  if (p.mfma) {
+    p.cols = (int)cols;
+    // token ranges (a power of two of them, each a multiple of 32 tokens and at least 128)
+    // so that there are a few hundred 256x256 tiles to spread over the compute units
+    const long long tiles = (long long)(c.M / 256) * (cols / 256);
+    int s = 1;
+    while ((long long)s * 2 * tiles <= 512 && (tokens / 32) % (s * 2) == 0 && tokens / (s * 2) >= 128)
+      s *= 2;
+    p.splits = s;
+    p.dzp_bytes = (size_t)tokens * cols * 2;
+    p.wgp_bytes = (size_t)c.M * cols * 2;
+    p.dxg_bytes = (size_t)tokens * c.M * 4;
+    p.partial_bytes = (size_t)s * c.M * cols * 4;
+  } else {
+    const long long s = (tokens + 511) / 512;
+    p.splits = (int)(s < 1 ? 1 : (s > 128 ? 128 : s));
+    p.dz_bytes = (size_t)tokens * c.E * 4;
+    p.partial_bytes = (size_t)p.splits * c.M * c.E * 4;
+  }
+  return p;
 }
 
 int launch_gate_bwd(const moe_config& c, const void* x, const float* wg, const float* gates,
                     const int32_t* expert_idx, const int32_t* slot, const float* dweight,
-                    const int32_t* c1, const float* daux, float* dz, float* dwg_partial,
-                    float* dwg, hipStream_t st) {
+                    const int32_t* c1, const float* daux, const GateBwdWs& w, float* dwg,
+                    hipStream_t st) {
+  const GateBwdPlan p = gate_bwd_plan(c);
   const long long tokens = (long long)c.G * c.S;
   const unsigned grid = (unsigned)((tokens + kRowsPerBlock - 1) / kRowsPerBlock);
   hipLaunchKernelGGL(gate_bwd_kernel, dim3(grid), dim3(256), 0, st, gates, expert_idx, slot,
-                     dweight, c1, daux, dz, c.S, c.E, tokens);
-  if (check_launch() != MOE_OK) return MOE_EHIP;
-  const int splits = dwg_splits(c);
-  long long tps = (tokens + splits - 1) / splits;
-  tps = (tps + 15) / 16 * 16;
-  const dim3 pgrid((unsigned)((c.M + 63) / 64), (unsigned)((c.E + 63) / 64), (unsigned)splits);
-  if (c.act_dtype == MOE_F32)
-    hipLaunchKernelGGL(dwg_partial_kernel<float>, pgrid, dim3(256), 0, st,
-                       static_cast<const float*>(x), dz, dwg_partial, c.M, c.E, tokens, tps);
-  else
-    hipLaunchKernelGGL(dwg_partial_kernel<bf16_t>, pgrid, dim3(256), 0, st,
-                       static_cast<const bf16_t*>(x), dz, dwg_partial, c.M, c.E, tokens, tps);
+                     dweight, c1, daux, p.mfma ? nullptr : w.dz, p.mfma ? w.dzp : nullptr, p.cols,
+                     c.S, c.E, tokens);
   if (check_launch() != MOE_OK) return MOE_EHIP;
   const long long size = (long long)c.M * c.E;
+  if (p.mfma) {
+    // dwg = x^T . dz as one batched MFMA GEMM over the token ranges, the three bf16 terms of
+    // dz side by side in the columns; the reduction adds ranges and terms in a fixed order
+    const int rc = launch_gemm_bf16_f32out(true, x, w.dzp, w.partial, p.splits, c.M, p.cols,
+                                           (int)(tokens / p.splits), st);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(dwg_reduce_kernel, dim3((unsigned)((size + 255) / 256)), dim3(256), 0, st,
+                       w.partial, dwg, c.M, c.E, p.cols, 3, p.splits);
+    return check_launch();
+  }
+  long long tps = (tokens + p.splits - 1) / p.splits;
+  tps = (tps + 15) / 16 * 16;
+  const dim3 pgrid((unsigned)((c.M + 63) / 64), (unsigned)((c.E + 63) / 64), (unsigned)p.splits);
+  if (c.act_dtype == MOE_F32)
+    hipLaunchKernelGGL(dwg_partial_kernel<float>, pgrid, dim3(256), 0, st,
+                       static_cast<const float*>(x), w.dz, w.partial, c.M, c.E, tokens, tps);
+  else
+    hipLaunchKernelGGL(dwg_partial_kernel<bf16_t>, pgrid, dim3(256), 0, st,
+                       static_cast<const bf16_t*>(x), w.dz, w.partial, c.M, c.E, tokens, tps);
+  if (check_launch() != MOE_OK) return MOE_EHIP;
   hipLaunchKernelGGL(dwg_reduce_kernel, dim3((unsigned)((size + 255) / 256)), dim3(256), 0, st,
-                     dwg_partial, dwg, size, splits);
+                     w.partial, dwg, c.M, c.E, c.E, 1, p.splits);
   return check_launch();
 }
 
-int launch_dx(const moe_config& c, const float* dz, const float* wg, const void* dbuf,
-              const int32_t* expert_idx, const int32_t* slot, void* dx, hipStream_t st) {
+int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int32_t* expert_idx,
+              const int32_t* slot, const GateBwdWs& w, void* dx, hipStream_t st) {
+  const GateBwdPlan p = gate_bwd_plan(c);
   const long long tokens = (long long)c.G * c.S;
+  if (p.mfma) {
+    // gate projection dz . wg^T on the matrix cores (fp32 result), then one pass that adds
+    // the gradient rows of the kept choices and rounds once
+    const long long n = (long long)c.M * p.cols;
+    hipLaunchKernelGGL(wg_pack_bwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
+                       w.wgp, c.M, c.E, p.cols);
+    if (check_launch() != MOE_OK) return MOE_EHIP;
+    const int rc = launch_gemm_bf16_f32out(false, w.dzp, w.wgp, w.dxg, 1, (int)tokens, c.M, p.cols, st);
+    if (rc != MOE_OK) return rc;
+    const unsigned grid = (unsigned)((tokens + kRowsPerBlock - 1) / kRowsPerBlock);
+    hipLaunchKernelGGL(dx_rows_kernel, dim3(grid), dim3(256), 0, st,
+                       reinterpret_cast<const float4*>(w.dxg), static_cast<const uint4*>(dbuf),
+                       expert_idx, slot, static_cast<uint4*>(dx), c.S, c.G, c.C, c.M / 8, tokens);
+    return check_launch();
+  }
   const dim3 grid((unsigned)((tokens + 63) / 64), (unsigned)((c.M + 63) / 64));
   if (grid.y > 65535) return MOE_EUNSUPPORTED;
   if (c.act_dtype == MOE_F32)
-    hipLaunchKernelGGL(dx_kernel<float>, grid, dim3(256), 0, st, dz, wg,
+    hipLaunchKernelGGL(dx_kernel<float>, grid, dim3(256), 0, st, w.dz, wg,
                        static_cast<const float*>(dbuf), expert_idx, slot, static_cast<float*>(dx),
                        c.S, c.G, c.C, c.M, c.E, tokens);
   else
-    hipLaunchKernelGGL(dx_kernel<bf16_t>, grid, dim3(256), 0, st, dz, wg,
+    hipLaunchKernelGGL(dx_kernel<bf16_t>, grid, dim3(256), 0, st, w.dz, wg,
                        static_cast<const bf16_t*>(dbuf), expert_idx, slot,
                        static_cast<bf16_t*>(dx), c.S, c.G, c.C, c.M, c.E, tokens);
   return check_launch();

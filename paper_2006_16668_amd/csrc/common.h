@@ -113,13 +113,28 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
                        const int32_t* src_token, const int32_t* expert_idx, const float* weight,
                        void* dout, float* dweight, hipStream_t st);
-int dwg_splits(const moe_config& c);
+// Gate gradients: on bf16 layers whose token count and M are multiples of 256 the two
+// projections (dwg = x^T dz, dz . wg^T) run on the matrix cores; otherwise fp32 FMA kernels.
+struct GateBwdPlan {
+  bool mfma;
+  int cols;     // mfma: columns of the 3-term bf16 copy of dz, 3E rounded up to 256
+  int splits;   // token ranges of the dwg partial sums
+  size_t dz_bytes, dzp_bytes, wgp_bytes, dxg_bytes, partial_bytes;
+};
+GateBwdPlan gate_bwd_plan(const moe_config& c);
+struct GateBwdWs {
+  float* dz;        // [N,E] fp32 (FMA path)
+  bf16_t* dzp;      // [N,cols] bf16 terms of dz (MFMA path)
+  bf16_t* wgp;      // [M,cols] bf16 wg repeated per term (MFMA path)
+  float* dxg;       // [N,M] fp32 gate part of dx (MFMA path)
+  float* partial;   // [splits,M,E or cols] fp32
+};
 int launch_gate_bwd(const moe_config& c, const void* x, const float* wg, const float* gates,
                     const int32_t* expert_idx, const int32_t* slot, const float* dweight,
-                    const int32_t* c1, const float* daux, float* dz, float* dwg_partial,
-                    float* dwg, hipStream_t st);
-int launch_dx(const moe_config& c, const float* dz, const float* wg, const void* dbuf,
-              const int32_t* expert_idx, const int32_t* slot, void* dx, hipStream_t st);
+                    const int32_t* c1, const float* daux, const GateBwdWs& w, float* dwg,
+                    hipStream_t st);
+int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int32_t* expert_idx,
+              const int32_t* slot, const GateBwdWs& w, void* dx, hipStream_t st);
 int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a_e, long long a_r,
                         long long a_k, const void* B, long long b_e, long long b_k, long long b_n,
                         void* Cout, const void* mask, int R, int N, int K, hipStream_t st);
@@ -136,6 +151,12 @@ int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, vo
                          hipStream_t st);
 int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
                          hipStream_t st);
+
+// batched bf16 MFMA GEMM with an fp32 result (expert_gemm.hip): transposed_a ? C = A^T.B with
+// A [batch,K,R], B [batch,K,N] : C = A.B^T with A [batch,R,K], B [batch,N,K]; C [batch,R,N]
+bool gemm_bf16_f32out_ok(int R, int N, int K);
+int launch_gemm_bf16_f32out(bool transposed_a, const void* A, const void* B, float* Cout,
+                            int batch, int R, int N, int K, hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 

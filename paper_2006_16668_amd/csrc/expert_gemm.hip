@@ -255,7 +255,8 @@ struct DmaSmem {
 //   data gradient C = A . B^T      A KC  [R,K],  B KC  [N,K]      (A_MNC = false, B_KC = true)
 //   weight grad.  C = A^T . B      A MNC [K,R],  B MNC [K,N]      (A_MNC = true,  B_KC = false)
 // EPI: 0 plain, 1 relu, 2 zero every element whose `mask` element (same [E,R,N] index as C)
-// is zero -- the derivative of relu taken from the stored activations.
+// is zero -- the derivative of relu taken from the stored activations, 3 plain with an fp32
+// result (Cout points to floats).
 template <int ST, int EPI, bool GATHER, bool A_MNC, bool B_KC>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
@@ -493,6 +494,23 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const uint32_t st_wr = st_base + r32 * 256 + 8 * (hh ^ (r32 >> 4));
     typedef u32x2_t __attribute__((address_space(3))) * lds_u2_ptr;
     typedef u32x4_t __attribute__((address_space(3))) * lds_u4_ptr;
+    if (EPI == 3) {
+      // fp32 result: Cout is a float array; each lane stores its 4 consecutive columns
+      float* Cf = reinterpret_cast<float*>(Cout) + c_off;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<f32x4_t*>(Cf + (size_t)(32 * i + r32) * N + 32 * j + 8 * q + 4 * hh) =
+                f32x4_t{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                        acc[i][j][4 * q + 3]};
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      continue;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       u32x4_t mk[8];
@@ -696,6 +714,22 @@ int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, vo
                           static_cast<float*>(h), c.E, R, c.H, c.M, st);
   return gemm_bf16<true>(static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(wi),
                          static_cast<bf16_t*>(h), c.E, R, c.H, c.M, st);
+}
+
+// Batched bf16 GEMM with an fp32 result for the gate gradients (A, B, C as in the kernel's
+// layout table; batch plays the role of the expert index).
+bool gemm_bf16_f32out_ok(int R, int N, int K) { return dma_shape_ok(R, N, K); }
+
+int launch_gemm_bf16_f32out(bool transposed_a, const void* A, const void* B, float* Cout,
+                            int batch, int R, int N, int K, hipStream_t st) {
+  if (!dma_shape_ok(R, N, K)) return MOE_EUNSUPPORTED;
+  auto a = static_cast<const bf16_t*>(A);
+  auto b = static_cast<const bf16_t*>(B);
+  auto c = reinterpret_cast<bf16_t*>(Cout);
+  // transposed_a: C = A^T . B with A [K,R], B [K,N];  else C = A . B^T with A [R,K], B [N,K]
+  return transposed_a
+             ? launch_bf16_dma<4, 3, false, true, false>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st)
+             : launch_bf16_dma<4, 3, false, false, true>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st);
 }
 
 bool expert_gemm1_can_gather(const moe_config& c) {

@@ -58,7 +58,7 @@ def test_backward_matches_oracle(cfg):
     _check(cfg, got, want, TOL[cfg.act_dtype])
 
 
-@pytest.mark.parametrize("name", ["tiny", "ragged_bf16", "gather_k128"])
+@pytest.mark.parametrize("name", ["tiny", "ragged_bf16", "gather_k128", "small"])
 def test_auxiliary_loss_gradient_alone(name):
     """dy = 0: expert-weight gradients vanish exactly, dx and dwg carry only the l_aux term,
     whose scale c_e/(E S^2) is far below the main term and would hide behind it otherwise."""
