@@ -40,8 +40,8 @@ B5  l_aux = (1/E) sum_e (c_e/S) m_e with m_e = (1/S) sum_s g_{s,e}: d l_aux / d 
 Parity pins (tests/test_oracle_backward.py): central finite differences of the
 FORWARD oracle on inputs whose routing does not change under the perturbation,
 torch.autograd (float64, CPU) on an independent dense restatement of the layer,
-closed forms (two experts with everything kept is a dense mixture; zero upstream
-gradient; a layer whose experts ignore their input).  Nothing is "parity unpinned".
+closed forms (two experts with everything kept is a dense mixture; the l_aux-only
+gradient; structure of the gradients).  Nothing is "parity unpinned".
 """
 from __future__ import annotations
 
