@@ -276,6 +276,20 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
   const int per_e = tiles_m * tiles_n;
   const int KT = K / BK;
+  // Tile t of an expert -> (row tile, column tile): bands of kBand row tiles, inside a band
+  // row tile fastest, then column tile.  The ~32 tiles an XCD works on at a time then span
+  // about 8 row tiles x 4 column tiles, the split that shares the most operand panels in that
+  // XCD's L2 (a tall output, as in the weight gradients, would otherwise re-read its A panel
+  // once per column tile).
+  constexpr int kBand = 8;
+#define MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                    \
+  int rt_, ct_;                                                                              \
+  {                                                                                          \
+    const int band_ = (t_) / (kBand * tiles_n), rem_ = (t_) - band_ * kBand * tiles_n;       \
+    const int left_ = tiles_m - band_ * kBand, rows_ = left_ < kBand ? left_ : kBand;        \
+    ct_ = rem_ / rows_;                                                                      \
+    rt_ = band_ * kBand + (rem_ - ct_ * rows_);                                              \
+  }
 
   // This block's tiles: XCD x = blockIdx % 8 owns a contiguous range of tiles; its
   // blocks take them round-robin, so at any time they work on neighbouring tiles
@@ -317,8 +331,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #define MOE_DMA_TOKENS(TILE)                                                                 \
   {                                                                                          \
     const int e_ = (TILE) / per_e, t_ = (TILE) - e_ * per_e;                                 \
+    MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                        \
+    (void)ct_;                                                                               \
     const uint64_t ta_ = (uint64_t)(uintptr_t)(                                              \
-        src_token + (size_t)e_ * R + (size_t)(t_ % tiles_m) * BM + 64 * wave + lane);        \
+        src_token + (size_t)e_ * R + (size_t)rt_ * BM + 64 * wave + lane);                   \
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"            \
                  :: "s"(lds_tok), "v"(ta_) : "memory");                                      \
   }
@@ -343,11 +359,12 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #define MOE_DMA_SET_SOURCES()                                                                \
   {                                                                                          \
     const int e_ = p_tile / per_e, t_ = p_tile - e_ * per_e;                                 \
-    if (GATHER) MOE_DMA_GATHER_ROWS(e_, (t_ % tiles_m) * BM)                                 \
-    else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)(t_ % tiles_m) * BM;              \
-    else p_a = A + ((size_t)e_ * R + (size_t)(t_ % tiles_m) * BM) * K;                       \
-    if (B_KC) p_b = B + ((size_t)e_ * N + (size_t)(t_ / tiles_m) * BN) * K;                  \
-    else p_b = B + (size_t)e_ * K * N + (size_t)(t_ / tiles_m) * BN;                         \
+    MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                        \
+    if (GATHER) MOE_DMA_GATHER_ROWS(e_, rt_ * BM)                                            \
+    else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)rt_ * BM;                         \
+    else p_a = A + ((size_t)e_ * R + (size_t)rt_ * BM) * K;                                  \
+    if (B_KC) p_b = B + ((size_t)e_ * N + (size_t)ct_ * BN) * K;                             \
+    else p_b = B + (size_t)e_ * K * N + (size_t)ct_ * BN;                                    \
   }
 #define MOE_DMA_ADVANCE()                                                                    \
   {                                                                                          \
@@ -486,7 +503,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     // row r at position c ^ (r & 15), its two 8-byte halves swapped when r >= 16 (then the
     // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
     const int e = c_tile / per_e, t = c_tile - e * per_e;
-    const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+    MOE_DMA_TILE_COORDS(t, rt, ct)
+    const int m0 = rt * BM, n0 = ct * BN;
     const size_t c_off = ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
     bf16_t* Ce = Cout + c_off;
     const uint32_t st_base = lds0 + (stage == 0 ? ST - 1 : stage - 1) * SM::kStage + wave * 8192;
@@ -545,6 +563,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
   }
 #undef MOE_DMA_SET_SOURCES
+#undef MOE_DMA_TILE_COORDS
 #undef MOE_DMA_GATHER_ROWS
 #undef MOE_DMA_TOKENS
 #undef MOE_DMA16_ADDR
