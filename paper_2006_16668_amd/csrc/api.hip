@@ -22,8 +22,8 @@ int check_config(const moe_config* c) {
 
 // Layout of the moe_forward workspace.
 struct ForwardWs {
-  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, gates, buf, h, out,
-      gate_ws, total;
+  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, gates, signbits, buf,
+      h, out, gate_ws, total;
 };
 
 ForwardWs carve(const moe_config& c) {
@@ -41,6 +41,7 @@ ForwardWs carve(const moe_config& c) {
   w.mean_gate = take(GE * 4);
   w.zero_row = take((size_t)c.M * elt);
   w.gates = take(N * c.E * 4);
+  w.signbits = take(moe::expert_gemm1_can_gather(c) ? moe::expert_signbits_bytes(c) : 0);
   w.buf = take(rows * c.M * elt);
   w.h = take(rows * c.H * elt);
   w.out = take(rows * c.M * elt);
@@ -115,7 +116,8 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
   rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
-                                                base + w.h, st)
+                                                base + w.h, keep_gates ? base + w.signbits : nullptr,
+                                                st)
               : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
   if (rc != MOE_OK) return rc;
   if (!mark(3)) return MOE_EHIP;
@@ -274,7 +276,9 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
                                dweight, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
-  rc = moe::launch_expert_dgrad2(*cfg, base + b.dout, wo, fb + f.h, base + b.dh, st);
+  rc = moe::launch_expert_dgrad2(*cfg, base + b.dout, wo, fb + f.h,
+                                 moe::expert_gemm1_can_gather(*cfg) ? fb + f.signbits : nullptr,
+                                 base + b.dh, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
   rc = moe::launch_expert_wgrad2(*cfg, fb + f.h, base + b.dout, dwo, st);

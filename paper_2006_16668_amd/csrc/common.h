@@ -106,8 +106,14 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
 // h = relu(dispatch(x) . wi) without materialising the dispatched buffer: the GEMM's copies
 // gather the rows of x through src_token (zero_row: M zeros of the activation type).
 bool expert_gemm1_can_gather(const moe_config& c);
+// signbits: NULL, or expert_signbits_bytes(c) bytes that receive one bit per element of h
+// (set where h > 0) in the GEMM kernel's private tile order, for launch_expert_dgrad2
 int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
-                               const void* zero_row, const void* wi, void* h, hipStream_t st);
+                               const void* zero_row, const void* wi, void* h, void* signbits,
+                               hipStream_t st);
+inline size_t expert_signbits_bytes(const moe_config& c) {
+  return (size_t)c.E * c.G * c.C * c.H / 8;
+}
 
 // backward pass (backward.hip); epi of the strided GEMM: 0 none, 1 relu, 2 zero where mask <= 0
 int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
@@ -140,11 +146,12 @@ int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a
                         void* Cout, const void* mask, int R, int N, int K, hipStream_t st);
 // expert GEMMs of the backward pass (expert_gemm.hip), per expert with rows = G*C:
 //   dgrad2: dh   = (dout . wo^T) masked by h > 0     [rows,M] x [H,M]^T -> [rows,H]
+//           (signbits as written by launch_expert_gemm1_gather when that path ran, else NULL)
 //   wgrad2: dwo  = h^T . dout                        [rows,H]^T x [rows,M] -> [H,M]
 //   dgrad1: dbuf = dh . wi^T                         [rows,H] x [M,H]^T -> [rows,M]
 //   wgrad1: dwi  = buf^T . dh                        [rows,M]^T x [rows,H] -> [M,H]
 int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
-                         void* dh, hipStream_t st);
+                         const void* signbits, void* dh, hipStream_t st);
 int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
                          hipStream_t st);
 int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,

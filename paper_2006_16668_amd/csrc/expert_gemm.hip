@@ -256,15 +256,24 @@ struct DmaSmem {
 //   weight grad.  C = A^T . B      A MNC [K,R],  B MNC [K,N]      (A_MNC = true,  B_KC = false)
 // EPI: 0 plain, 1 relu, 2 zero every element whose `mask` element (same [E,R,N] index as C)
 // is zero -- the derivative of relu taken from the stored activations, 3 plain with an fp32
-// result (Cout points to floats).
+// result (Cout points to floats), 4 relu that also records which results are non-zero, one
+// bit per element in `signbits`, 5 zero every element whose recorded bit is clear.
+// The bit record is private to this kernel: 8 KB per 256x256 tile (tile index
+// (e * tiles_m + row tile) * tiles_n + column tile), inside a tile 2 KB per wavefront laid
+// out as [2][64 lanes][16 bytes] = the 32 bytes a lane meets in its own store phase (4 row
+// groups x 8 stores, one byte each: bit b = column 8 c + b of that store).  Writer and reader
+// are the same tiling of the same [E,R,N] matrix, so no lane ever needs another lane's bits.
+// The reader fetches a tile's 8 KB into spare LDS with two register-bypassing copies issued
+// in the tile's first K step; the waits of the next two steps cover them.
 template <int ST, int EPI, bool GATHER, bool A_MNC, bool B_KC>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
     int R, int N, int K, int tiles_m, int tiles_n, int ntiles,
     const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
-    uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask) {
+    uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask,
+    unsigned char* __restrict__ signbits) {
   static_assert(!(GATHER && A_MNC), "the gather form addresses whole rows of a K-contiguous A");
-  constexpr bool RELU = EPI == 1;
+  constexpr bool RELU = EPI == 1 || EPI == 4;
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -327,6 +336,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // cover it) and read from there when the producer moves on to that tile.
   uint64_t a_addr[4];
   const uint32_t lds_tok = lds0 + (uint32_t)SM::kBytes + wave * 256;
+  const uint32_t lds_bits = lds0 + (uint32_t)SM::kBytes + wave * 2048;   // EPI 5 (never with GATHER)
   typedef int __attribute__((address_space(3))) * lds_int_ptr;
 #define MOE_DMA_TOKENS(TILE)                                                                 \
   {                                                                                          \
@@ -476,6 +486,14 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       __syncthreads();
+      if (EPI == 5 && kt == 0) {
+        const int e5 = c_tile / per_e, t5 = c_tile - e5 * per_e;
+        MOE_DMA_TILE_COORDS(t5, rt5, ct5)
+        const unsigned char* src5 = signbits + ((size_t)(e5 * tiles_m + rt5) * tiles_n + ct5) * 8192 +
+                                    wave * 2048 + lane * 16;
+        MOE_DMA16_ADDR(lds_bits, (uint64_t)(uintptr_t)src5);
+        MOE_DMA16_ADDR(lds_bits + 1024, (uint64_t)(uintptr_t)(src5 + 1024));
+      }
       const int nstage = stage + 1 == ST ? 0 : stage + 1;      // stage of step g+1
       int more = __builtin_amdgcn_readfirstlane(p_g < G);      // p_stage: stage of step g-1, free now
       asm volatile("" : "+s"(more));
@@ -529,6 +547,11 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       }
       continue;
     }
+    u32x4_t bits[2] = {u32x4_t{0u, 0u, 0u, 0u}, u32x4_t{0u, 0u, 0u, 0u}};
+    if (EPI == 5) {
+      bits[0] = *(lds_u4_ptr)(uintptr_t)(lds_bits + lane * 16);
+      bits[1] = *(lds_u4_ptr)(uintptr_t)(lds_bits + 1024 + lane * 16);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       u32x4_t mk[8];
@@ -557,9 +580,28 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
           for (int w = 0; w < 4; ++w)
             d[w] &= ((mk[ps][w] & 0xffffu) ? 0xffffu : 0u) | ((mk[ps][w] >> 16) ? 0xffff0000u : 0u);
         }
+        if (EPI == 4) {
+          uint32_t byte = 0;
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            byte |= ((d[w] & 0xffffu) ? 1u : 0u) << (2 * w) | ((d[w] >> 16) ? 2u : 0u) << (2 * w);
+          bits[i >> 1][2 * (i & 1) + (ps >> 2)] |= byte << (8 * (ps & 3));
+        }
+        if (EPI == 5) {
+          const uint32_t byte = bits[i >> 1][2 * (i & 1) + (ps >> 2)] >> (8 * (ps & 3));
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            d[w] &= ((byte >> (2 * w)) & 1u ? 0xffffu : 0u) | ((byte >> (2 * w + 1)) & 1u ? 0xffff0000u : 0u);
+        }
         *reinterpret_cast<u32x4_t*>(Ce + (size_t)(32 * i + rr) * N + 8 * c) = d;
       }
       __builtin_amdgcn_sched_barrier(0);   // one row group at a time: small register need
+    }
+    if (EPI == 4) {
+      unsigned char* dst4 = signbits + ((size_t)(e * tiles_m + rt) * tiles_n + ct) * 8192 +
+                            wave * 2048 + lane * 16;
+      *reinterpret_cast<u32x4_t*>(dst4) = bits[0];
+      *reinterpret_cast<u32x4_t*>(dst4 + 1024) = bits[1];
     }
   }
 #undef MOE_DMA_SET_SOURCES
@@ -579,9 +621,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 template <int ST, int EPI, bool GATHER, bool A_MNC = false, bool B_KC = false>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
                     const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st,
-                    const bf16_t* mask = nullptr) {
+                    const bf16_t* mask = nullptr, unsigned char* signbits = nullptr) {
   using SM = DmaSmem<ST>;
-  constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0);
+  static_assert(!(GATHER && EPI == 5), "the two users of the spare LDS exclude each other");
+  constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0) + (EPI == 5 ? 8192 : 0);
   // n / C for n < 2^31 as (n * c_magic) >> (32 + c_shift), c_magic = ceil(2^(31+l) / C) with
   // l = ceil(log2 C); C == 1 is flagged by c_magic == 0
   uint32_t c_magic = 0;
@@ -610,7 +653,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
-                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask);
+                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask, signbits);
   return check_launch();
 }
 
@@ -759,8 +802,14 @@ bool expert_gemm1_can_gather(const moe_config& c) {
 }
 
 int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
-                               const void* zero_row, const void* wi, void* h, hipStream_t st) {
+                               const void* zero_row, const void* wi, void* h, void* signbits,
+                               hipStream_t st) {
   if (!expert_gemm1_can_gather(c)) return MOE_EUNSUPPORTED;
+  if (signbits != nullptr)
+    return launch_bf16_dma<4, 4, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
+                                       static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
+                                       static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr,
+                                       static_cast<unsigned char*>(signbits));
   return launch_bf16_dma<4, 1, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
                                         static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
                                         static_cast<const bf16_t*>(zero_row), c.S, c.C, st);
@@ -780,8 +829,14 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
 
 // ---- backward pass: A K-contiguous x B K-contiguous (dgrad), A and B row(k)-major (wgrad) ----
 int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
-                         void* dh, hipStream_t st) {
+                         const void* signbits, void* dh, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  // the forward pass recorded the sign bits exactly when its first GEMM gathered (K >= 128)
+  if (signbits != nullptr && expert_gemm1_can_gather(c))
+    return launch_bf16_dma<4, 5, false, false, true>(
+        static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
+        c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, nullptr,
+        const_cast<unsigned char*>(static_cast<const unsigned char*>(signbits)));
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.H, c.M))
     return launch_bf16_dma<4, 2, false, false, true>(
         static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),

@@ -30,8 +30,9 @@ def test_host_only_entry_points():
     sh = moe.MoEShape(8, 4096, 1024, 8192, 32, 256, "bf16")
     rows = sh.E * sh.G * sh.C
     need = rows * (2 * sh.M + sh.H) * 2           # buf + out + h
+    need += rows * sh.H // 8                      # one bit per element of h, kept for the backward pass
     got = moe.moe_workspace_bytes(sh)
-    assert need < got < need + (64 << 20)
+    assert need < got < need + (16 << 20)
     assert 0 < moe.moe_gate_workspace_bytes(sh) < got
     # the paper-size bf16 layer gathers inside the first GEMM; fp32 and short rows do not
     assert moe.moe_forward_fuses_dispatch(sh) is True
