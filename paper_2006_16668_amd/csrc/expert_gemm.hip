@@ -473,18 +473,22 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #pragma unroll
       for (int i = 0; i < TM; ++i) { MOE_DMA_MFMA_ROW(fr[0], i) }
       // The own copies of step g+1 must have landed; younger steps (8 copies each) may
-      // still fly.  p_g steps have been started.  Loads and stores do not complete in
-      // order with respect to each other, so after an epilogue everything is awaited.
+      // still fly.  p_g steps have been started.  Copies land in the order they were issued,
+      // but stores complete in no fixed order relative to them: "at most n operations
+      // outstanding" therefore still proves that all but the n youngest copies have landed,
+      // it just may wait for stores as well.  An epilogue first awaits every copy issued so
+      // far (steps up to g+3) and only then issues its stores, so the first two steps of the
+      // following tile need no wait at all and the stores drain behind their MFMAs.
       // (The counts pass through an empty asm so that the optimiser cannot peel or
       // duplicate the loop body around these conditions: copies of the body would shuffle
       // the 256 accumulator registers between them.)
       int younger = p_g - 1 - (g + 1 < G ? g + 1 : G - 1);
-      if (kt == 0 && g > 0) younger = 0;                       // stores of the previous tile
+      if (kt < 2 && c_tile != first) younger = 3;              // landed before the last epilogue
       younger = __builtin_amdgcn_readfirstlane(younger);
       asm volatile("" : "+s"(younger));
       if (younger <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else if (younger == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       __syncthreads();
       if (EPI == 5 && kt == 0) {
         const int e5 = c_tile / per_e, t5 = c_tile - e5 * per_e;
@@ -520,6 +524,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     // full-row 16-byte stores.  Staging layout: [32 rows][16 chunks of 16 bytes], chunk c of
     // row r at position c ^ (r & 15), its two 8-byte halves swapped when r >= 16 (then the
     // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // every copy issued so far
     const int e = c_tile / per_e, t = c_tile - e * per_e;
     MOE_DMA_TILE_COORDS(t, rt, ct)
     const int m0 = rt * BM, n0 = ct * BN;
