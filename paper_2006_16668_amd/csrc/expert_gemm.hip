@@ -25,6 +25,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
+constexpr int kMaxDevices = 64;   // devices one process can address (per-device launch caches)
 constexpr int kXcds = 8;
 
 __device__ __forceinline__ int xcd_remap(int bid, int nblk) {
@@ -641,18 +642,20 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
     c_shift = l - 1;
   }
   auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC>;
-  static bool attr_set = false;   // idempotent: a repeated call sets the same value
-  static int cus = 0;
-  if (!attr_set) {
+  // per device, once: the kernel's LDS limit and the number of compute units.  The cached
+  // values are constants of the device, so a race between two first calls is harmless.
+  static int cus_of[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
+  if (cus_of[dev] == 0) {
+    int n = 0;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
       return MOE_EHIP;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-      return MOE_EHIP;
-    attr_set = true;
+    cus_of[dev] = n;
   }
+  const int cus = cus_of[dev];
   const int tiles_m = R / 256, tiles_n = N / 256;
   const long long ntiles = (long long)E * tiles_m * tiles_n;
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
@@ -673,12 +676,14 @@ int launch_bf16_kernel(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, in
                        hipStream_t st) {
   using SM = GemmSmem<BM, BN, BK>;
   auto kern = expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>;
-  static bool attr_set = false;   // idempotent: a repeated call sets the same value
-  if (!attr_set) {
+  static bool attr_set[kMaxDevices] = {};   // per device; setting it twice is harmless
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytes) != hipSuccess)
       return MOE_EHIP;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   const int tiles_m = (R + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long nblk = (long long)E * tiles_m * tiles_n;

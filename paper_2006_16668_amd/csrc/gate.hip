@@ -288,11 +288,12 @@ __device__ __forceinline__ void gate_chunk_epilogue(
 #define MOE_GATE_MFMA(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16( \
     __builtin_bit_cast(bf16x8_t, A), __builtin_bit_cast(bf16x8_t, B), C, 0, 0, 0)
 
-// Narrow gates (E <= 64): a block is one chunk of 64 tokens; wavefront w owns the
-// 32 tokens of half w&1 and half w>>1 of the feature dimension, all experts.  x goes
-// from global memory straight into the A operand (a lane reads 64 contiguous bytes of
-// its token row per 64-feature block), four blocks ahead of the multiply, so that a
-// chunk of only 64 tokens keeps enough bytes in flight; the two partial sums meet in LDS.
+// Narrow gates (E <= 64), two chunks per block: 128 tokens, wavefront w owns quarter w of the feature
+// dimension and all four 32-token row tiles, so that one fetch of a packed weight fragment
+// (3 KB per MFMA step from L2) feeds 12 MFMAs instead of 3: with one chunk per block the
+// weight fragments cost three times the L2 traffic of x itself.  x goes from global memory
+// straight into the A operand, two 64-feature blocks ahead; the four partial sums meet in LDS
+// and are added in a fixed order.
 template <int ET>
 __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
@@ -300,73 +301,105 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int Epad = 32 * ET, pitch = Epad + 1, PD = 4;
-  __shared__ float zs[64 * pitch];
-  __shared__ float part[64 * pitch];
-  __shared__ int hh[2 * Epad];
-  const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
+  constexpr int Epad = 32 * ET, pitch = Epad + 1, PD = 2;
+  extern __shared__ __attribute__((aligned(16))) unsigned char gate_smem[];
+  float* part = reinterpret_cast<float*>(gate_smem);            // [4][128 * pitch]
+  int* hh = reinterpret_cast<int*>(part + 4 * 128 * pitch);      // [2 * Epad]
+  const int npair = (nch + 1) / 2;
+  const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int th = wave & 1, kh = wave >> 1;
   const int r = lane & 31, h = lane >> 5;
-  int s = ch * kChunk + th * 32 + r;
-  s = s < S ? s : S - 1;                              // clamp: surplus rows are ignored later
-  const bf16_t* xrow = x + ((size_t)g * S + s) * M;    // row start
-  const int KB = (M + 63) / 64, KB0 = (KB + 1) / 2;
-  const int kb0 = kh == 0 ? 0 : KB0, kb1 = kh == 0 ? KB0 : KB;
+  const bf16_t* xrow[4];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt) {
+    int s = pr * 128 + 32 * rt + r;
+    s = s < S ? s : S - 1;                            // clamp: surplus rows are ignored later
+    xrow[rt] = x + ((size_t)g * S + s) * M;
+  }
+  const int KB = (M + 63) / 64, KBq = (KB + 3) / 4;
+  const int kb0 = wave * KBq < KB ? wave * KBq : KB;
+  const int kb1 = kb0 + KBq < KB ? kb0 + KBq : KB;
 
-  f32x16_t acc[ET];
+  f32x16_t acc[4][ET];
 #pragma unroll
-  for (int t = 0; t < ET; ++t)
+  for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    for (int t = 0; t < ET; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
 
   // Loads are unconditional: a block index past this wavefront's range is clamped (its
   // data is never multiplied) and features past M read the row start instead (they meet
   // zero weights in the packed operand).
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-  u32x4_t a[PD][4];
-#define MOE_GATE_LOAD_X(P, KBI)                                                       \
-  _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                     \
+  u32x4_t a[PD][4][4];
+#define MOE_GATE_LOAD_X2(P, KBI)                                                      \
+  {                                                                                   \
     int kbc_ = (KBI) < kb1 ? (KBI) : kb1 - 1;                                         \
     kbc_ = kbc_ < 0 ? 0 : kbc_;                                                       \
-    const int col_ = kbc_ * 64 + 32 * h + 8 * j;                                      \
-    a[P][j] = *reinterpret_cast<const u32x4_t*>(xrow + (col_ < M ? col_ : 0));        \
+    _Pragma("unroll") for (int rt = 0; rt < 4; ++rt)                                  \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                 \
+        const int col_ = kbc_ * 64 + 32 * h + 8 * j;                                  \
+        a[P][rt][j] = *reinterpret_cast<const u32x4_t*>(xrow[rt] + (col_ < M ? col_ : 0)); \
+      }                                                                               \
   }
+  // Vector loads come back in the order they were issued, so a weight fragment requested
+  // just before its MFMA would wait behind every x row requested earlier (HBM latency each
+  // time).  The weight fragments of a whole super-block of SB feature blocks are therefore
+  // requested first (they hit in L2), then the x rows, PD blocks ahead of their use.
+  constexpr int SB = 4 / ET;
+  for (int sb0 = kb0; sb0 < kb1; sb0 += SB) {
+    u32x4_t b[SB][4][ET * 3];
 #pragma unroll
-  for (int p = 0; p < PD; ++p) { MOE_GATE_LOAD_X(p, kb0 + p) }
-  for (int kb = kb0; kb < kb1; kb += PD) {
+    for (int q = 0; q < SB; ++q) {
+      const int cur = sb0 + q < kb1 ? sb0 + q : kb1 - 1;
 #pragma unroll
-    for (int p = 0; p < PD; ++p) {
-      const int cur = kb + p;
-      if (cur < kb1) {                                // wave-uniform
+      for (int j = 0; j < 4; ++j) {
+        const u32x4_t* bp = reinterpret_cast<const u32x4_t*>(wgP) + (size_t)((cur * 4 + j) * ET) * 3 * 64 + lane;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint4* bp = wgP + (size_t)((cur * 4 + j) * ET) * 3 * 64 + lane;
-#pragma unroll
-          for (int t = 0; t < ET; ++t) {
-            const uint4 b0 = bp[(t * 3 + 0) * 64], b1 = bp[(t * 3 + 1) * 64], b2 = bp[(t * 3 + 2) * 64];
-            acc[t] = MOE_GATE_MFMA(a[p][j], b2, acc[t]);
-            acc[t] = MOE_GATE_MFMA(a[p][j], b1, acc[t]);
-            acc[t] = MOE_GATE_MFMA(a[p][j], b0, acc[t]);
-          }
-        }
+        for (int t = 0; t < ET * 3; ++t) b[q][j][t] = bp[t * 64];
       }
-      MOE_GATE_LOAD_X(p, cur + PD)
+    }
+#pragma unroll
+    for (int p = 0; p < PD; ++p) MOE_GATE_LOAD_X2(p, sb0 + p)
+#pragma unroll
+    for (int q = 0; q < SB; ++q) {
+      if (sb0 + q < kb1) {                            // wave-uniform
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int t = 0; t < ET; ++t)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) {
+              acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 2], acc[rt][t]);
+              acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 1], acc[rt][t]);
+              acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 0], acc[rt][t]);
+            }
+      }
+      if (q + PD < SB) MOE_GATE_LOAD_X2(q % PD, sb0 + q + PD)
     }
   }
-#undef MOE_GATE_LOAD_X
-  // acc[t][i]: token row 8 (i/4) + 4 h + i%4 of this wave's half, expert 32 t + r
-  float* dst = kh == 0 ? zs : part;
+#undef MOE_GATE_LOAD_X2
+  // acc[rt][t][i]: token row 32 rt + 8 (i/4) + 4 h + i%4, expert 32 t + r
+  float* dst = part + (size_t)wave * 128 * pitch;
 #pragma unroll
-  for (int t = 0; t < ET; ++t)
+  for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      dst[(th * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[t][i];
+    for (int t = 0; t < ET; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        dst[(32 * rt + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[rt][t][i];
   __syncthreads();
-  for (int i = threadIdx.x; i < 64 * pitch; i += 256) zs[i] += part[i];
+  for (int i = threadIdx.x; i < 128 * pitch; i += 256)
+    part[i] = (part[i] + part[128 * pitch + i]) + (part[2 * 128 * pitch + i] + part[3 * 128 * pitch + i]);
   __syncthreads();
-  gate_chunk_epilogue<256>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
-                           hist1, hist2, msum, hh, hh + Epad);
+#pragma unroll 1
+  for (int c = 0; c < 2; ++c) {
+    const int ch = 2 * pr + c;
+    if (ch < nch)                                     // block-uniform
+      gate_chunk_epilogue<256>(part + (size_t)c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx,
+                               slot, weight, gates_opt, hist1, hist2, msum, hh, hh + Epad);
+  }
 }
 
 // Wide gates (64 < E <= 512): the NW wavefronts of a block share 128 tokens (staged
@@ -678,11 +711,25 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
     hipLaunchKernelGGL(gate_pack_wg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        wg, wgP, c.M, c.E, pg.T, total);
     if ((rc = check_launch()) != MOE_OK) return rc;
-    const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), grid_rows((unsigned)(c.G * nch)), block(256);
+    const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), block(256);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
-    if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid_rows, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 64) hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid_rows, block, 0, st, MOE_GATE_ARGS);
+    if (c.E <= 64) {
+      const size_t lds1 = (4 * 128 * 33 + 2 * 32) * 4, lds2 = (4 * 128 * 65 + 2 * 64) * 4;
+      static bool lds_set[64] = {};                   // per device; setting it twice is harmless
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_EHIP;
+      if (!lds_set[dev]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gate_mfma_rows_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(gate_mfma_rows_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2) != hipSuccess)
+          return MOE_EHIP;
+        lds_set[dev] = true;
+      }
+      if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, lds1, st, MOE_GATE_ARGS);
+      else hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, lds2, st, MOE_GATE_ARGS);
+    }
     else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_kernel<1, 4, 3>), grid, block, 0, st, MOE_GATE_ARGS);
     else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 4, 2>), grid, block, 0, st, MOE_GATE_ARGS);
     else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
