@@ -43,10 +43,13 @@ __device__ __forceinline__ void wave_argmax(float& bv, int& bi) {
 
 // One block = one chunk of 64 tokens of one group; wave w takes tokens w, w+4, ...
 // Lane l owns experts l, l+64, ... (EPL of them).
-template <typename T, int EPL>
+// PRE: the logits were computed beforehand on the matrix cores (very wide gates): zpre
+// [tokens, cols] holds, for expert e, the three partial logits x . (hi, mid, lo term of wg) in
+// columns 3e, 3e+1, 3e+2; they are added smallest term first.
+template <typename T, int EPL, bool PRE>
 __global__ __launch_bounds__(256) void gate_topk_kernel(
     const T* __restrict__ x, const float* __restrict__ wg, const float* __restrict__ u,
-    int S, int M, int E, int nch,
+    const float* __restrict__ zpre, int cols, int S, int M, int E, int nch,
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
@@ -54,7 +57,7 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(
   const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float* xs = reinterpret_cast<float*>(smem) + (size_t)wave * M;  // this wave's token row
-  float* msum_l = reinterpret_cast<float*>(smem) + (size_t)4 * M;  // [4][E]
+  float* msum_l = reinterpret_cast<float*>(smem) + (PRE ? 0 : (size_t)4 * M);  // [4][E]
   int* h1 = reinterpret_cast<int*>(msum_l + (size_t)4 * E);
   int* h2 = h1 + E;
   for (int e = threadIdx.x; e < E; e += 256) { h1[e] = 0; h2[e] = 0; }
@@ -68,20 +71,30 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(
     const bool valid = s < S;
     const size_t n = (size_t)g * S + (valid ? s : 0);
     __syncthreads();  // previous row fully consumed (also orders the histogram zeroing)
-    for (int m = lane; m < M; m += 64) xs[m] = Elt<T>::load(x + n * M + m);
+    if (!PRE)
+      for (int m = lane; m < M; m += 64) xs[m] = Elt<T>::load(x + n * M + m);
     __syncthreads();
     if (!valid) continue;  // both barriers of the next iteration are still reached
 
     float z[EPL];
 #pragma unroll
     for (int j = 0; j < EPL; ++j) z[j] = 0.f;
-    for (int m = 0; m < M; ++m) {
-      const float xv = xs[m];
-      const float* wrow = wg + (size_t)m * E;
+    if (PRE) {
+      const float* zp = zpre + n * cols;
 #pragma unroll
       for (int j = 0; j < EPL; ++j) {
         const int e = lane + 64 * j;
-        if (e < E) z[j] = fmaf(xv, wrow[e], z[j]);
+        if (e < E) z[j] = (zp[3 * e + 2] + zp[3 * e + 1]) + zp[3 * e];
+      }
+    } else {
+      for (int m = 0; m < M; ++m) {
+        const float xv = xs[m];
+        const float* wrow = wg + (size_t)m * E;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+          const int e = lane + 64 * j;
+          if (e < E) z[j] = fmaf(xv, wrow[e], z[j]);
+        }
       }
     }
     // top-2 on the logits (softmax is monotone); ties go to the lowest index
@@ -647,17 +660,19 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
   if (s2 >= 0) src_token[((size_t)e2 * G + g) * C + s2] = s;
 }
 
-template <typename T>
+template <typename T, bool PRE = false>
 int launch_topk(const moe_config& c, int nch, const T* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, float* gates_opt,
-                int32_t* hist1, int32_t* hist2, float* msum, hipStream_t st) {
-  const size_t shm = ((size_t)4 * c.M + (size_t)4 * c.E) * sizeof(float) + (size_t)2 * c.E * sizeof(int);
-  if (shm > 160 * 1024) return MOE_EUNSUPPORTED;
+                int32_t* hist1, int32_t* hist2, float* msum, hipStream_t st,
+                const float* zpre = nullptr, int cols = 0) {
+  const size_t shm = ((PRE ? 0 : (size_t)4 * c.M) + (size_t)4 * c.E) * sizeof(float) +
+                     (size_t)2 * c.E * sizeof(int);
+  if (shm > 64 * 1024) return MOE_EUNSUPPORTED;   // the default dynamic LDS limit of a kernel
   const dim3 grid((unsigned)(c.G * nch)), block(256);
   const int epl = (c.E + 63) / 64;
 #define MOE_GATE_CASE(N)                                                                        \
-  hipLaunchKernelGGL((gate_topk_kernel<T, N>), grid, block, shm, st, x, wg, u, c.S, c.M, c.E,  \
-                     nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum)
+  hipLaunchKernelGGL((gate_topk_kernel<T, N, PRE>), grid, block, shm, st, x, wg, u, zpre, cols, \
+                     c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum)
   if (epl <= 1) MOE_GATE_CASE(1);
   else if (epl <= 2) MOE_GATE_CASE(2);
   else if (epl <= 4) MOE_GATE_CASE(4);
@@ -670,6 +685,44 @@ int launch_topk(const moe_config& c, int nch, const T* x, const float* wg, const
 }
 
 }  // namespace
+
+// Very wide gates (E > 512): wgk[3e+p, m] = term p of wg[m,e] (hi, mid, lo bf16 terms), rows
+// past 3E zero: the K-contiguous B operand of a plain GEMM x . wgk^T whose fp32 result holds the
+// three partial logits of every expert side by side.
+namespace {
+__global__ __launch_bounds__(256) void gate_pack_wide_kernel(
+    const float* __restrict__ wg, bf16_t* __restrict__ wgk, int M, int E, int cols) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)cols * M) return;
+  const int c = (int)(i / M), m = (int)(i % M);
+  bf16_t out = 0;
+  if (c < 3 * E) {
+    const float v = wg[(size_t)m * E + c / 3];
+    const bf16_t hi = f32_to_bf16(v);
+    const float r1 = v - bf16_to_f32(hi);
+    const bf16_t mid = f32_to_bf16(r1);
+    const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+    out = c % 3 == 0 ? hi : (c % 3 == 1 ? mid : lo);
+  }
+  wgk[i] = out;
+}
+}  // namespace
+
+// E > 512 on the matrix cores: needs the persistent GEMM's shapes (token count a multiple of
+// 256, M of 32) and at most 2048 experts (registers of the epilogue kernel).
+struct WideGeom { int cols; size_t z_bytes, w_bytes; };
+static WideGeom wide_geom(const moe_config& c) {
+  WideGeom w{};
+  const long long tokens = (long long)c.G * c.S;
+  const long long cols = ((long long)3 * c.E + 255) / 256 * 256;
+  if (c.act_dtype != MOE_BF16 || c.E <= 512 || c.E > 2048 || tokens > 0x7fffffffLL ||
+      !gemm_bf16_f32out_ok((int)tokens, (int)cols, c.M))
+    return w;
+  w.cols = (int)cols;
+  w.z_bytes = (size_t)tokens * cols * 4;
+  w.w_bytes = (size_t)cols * c.M * 2;
+  return w;
+}
 
 // Geometry of the packed gate weights (bf16 MFMA path).
 struct PackGeom { int T, KS; size_t bytes; };
@@ -685,7 +738,9 @@ static PackGeom pack_geom(const moe_config& c) {
 
 size_t gate_workspace_bytes(const moe_config& c) {
   const size_t nch = (size_t)(c.S + kChunk - 1) / kChunk;
-  return 3 * align_up((size_t)c.G * nch * c.E * 4, 256) + align_up(pack_geom(c).bytes, 256);
+  const WideGeom w = wide_geom(c);
+  return 3 * align_up((size_t)c.G * nch * c.E * 4, 256) + align_up(pack_geom(c).bytes, 256) +
+         align_up(w.w_bytes, 256) + align_up(w.z_bytes, 256);
 }
 
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
@@ -703,6 +758,19 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
   if (c.act_dtype == MOE_F32) {
     rc = launch_topk<float>(c, nch, static_cast<const float*>(x), wg, u, expert_idx, slot, weight,
                             gates_opt, hist1, hist2, msum, st);
+  } else if (wide_geom(c).cols != 0) {
+    // pg.bytes == 0 here: the packed-operand region is empty, wgk and the logits follow it
+    const WideGeom w = wide_geom(c);
+    bf16_t* wgk = reinterpret_cast<bf16_t*>(wgP);
+    float* zpre = reinterpret_cast<float*>(reinterpret_cast<char*>(wgP) + align_up(w.w_bytes, 256));
+    const long long n = (long long)w.cols * c.M;
+    hipLaunchKernelGGL(gate_pack_wide_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
+                       wgk, c.M, c.E, w.cols);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    rc = launch_gemm_bf16_f32out(false, x, wgk, zpre, 1, c.G * c.S, w.cols, c.M, st);
+    if (rc != MOE_OK) return rc;
+    rc = launch_topk<bf16_t, true>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
+                                   weight, gates_opt, hist1, hist2, msum, st, zpre, w.cols);
   } else if (pg.bytes == 0) {
     rc = launch_topk<bf16_t>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
                              weight, gates_opt, hist1, hist2, msum, st);

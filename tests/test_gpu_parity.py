@@ -51,6 +51,10 @@ SMALL_CASES = [
     # that straddle groups and mostly empty slots; capacity 1; more tiles than compute units
     MoEConfig("gather_k128", G=16, S=100, M=128, H=256, E=8, C=48, act_dtype="bf16", seed=31),
     MoEConfig("gather_c1", G=256, S=4, M=160, H=256, E=3, C=1, act_dtype="bf16", seed=32),
+    # more than 512 experts (the paper goes to 2048 per layer): logits as one GEMM on the matrix
+    # cores with wg in three bf16 terms, then a per-token softmax / top-2 pass
+    MoEConfig("e640_wide", G=2, S=512, M=256, H=32, E=640, C=2, act_dtype="bf16", seed=34),
+    MoEConfig("e2048_wide", G=1, S=1024, M=128, H=32, E=2048, C=1, act_dtype="bf16", seed=35),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
 ]
 
