@@ -164,8 +164,11 @@ def main():
 
     ms_per_step = (t1 - t0) * 1e3 / K
     names = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
-    stage_ms = {n: sum(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K)) / K
+    per_call = {n: sorted(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K))
                 for i, n in enumerate(names)}
+    stage_ms = {n: sum(v) / K for n, v in per_call.items()}
+    stage_median = {n: v[K // 2] for n, v in per_call.items()}
+    stage_min = {n: v[0] for n, v in per_call.items()}
     elt = 2 if cfg.act_dtype == "bf16" else 4
     flops_launch = 2.0 * cfg.M * cfg.H * kept_rows            # per GEMM launch, kept rows only
     dom = max(("expert_gemm1", "expert_gemm2"), key=lambda n: stage_ms[n])
@@ -194,7 +197,11 @@ def main():
                      "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
                      "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
-        "stages_ms": stage_ms,
+        "stages_ms": stage_ms, "stages_ms_median": stage_median, "stages_ms_min": stage_min,
+        # the gate's logits run as three bf16 MFMA passes (wg in three bf16 terms): at E > 64 that,
+        # not HBM, bounds the stage
+        "gate_mfma_frac": (2.0 * 3 * cfg.N * cfg.M * cfg.E / (stage_ms["gate"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+                           if cfg.act_dtype == "bf16" else None),
         "stages_hbm_frac": {n: hbm_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS
                             for n in hbm_bytes},
         "ffn_mfma_frac": 2 * flops_launch / ((stage_ms["expert_gemm1"] + stage_ms["expert_gemm2"]) * 1e-3)
