@@ -542,6 +542,143 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
                             hist1, hist2, msum, hh, hh + Epad);
   }
 }
+// Wide gates, 64 < E <= 256: as gate_mfma_cols_kernel, but the x rows are fetched by four
+// extra wavefronts that do nothing else.  Vector loads of one wavefront return in issue order,
+// so in a wavefront that fetches both, every L2-resident weight fragment requested after an x
+// block waits for that block's HBM latency; split by role, the multiplying wavefronts only wait
+// for L2.  The loader wavefronts keep a ring of RD feature blocks in flight (global -> registers
+// -> LDS stage); both roles pass the same barriers, one per 64-feature block.
+template <int ETW, int PB>
+__global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
+    const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
+    int S, int M, int E, int nch,
+    int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
+    float* __restrict__ gates_opt,
+    int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
+  constexpr int NW = 4, NT = 512, T = ETW * NW, Epad = 32 * T, pitch = Epad + 1;
+  constexpr int AV = 4, RD = 8;                        // loader: 16-byte vectors per thread and block
+  constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
+  constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
+  constexpr int kZBytes = 64 * pitch * 4;              // logits of one chunk
+  constexpr int kUnion = kABytes > kZBytes ? kABytes : kZBytes;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kUnion];
+  __shared__ int hh[2 * Epad];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);
+  float* zs = reinterpret_cast<float*>(smem);
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+  const int npair = (nch + 1) / 2;
+  const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int KB = (M + 63) / 64;
+
+  f32x16_t acc[4][ETW];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int t = 0; t < ETW; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
+
+  if (wave >= NW) {
+    // ---- loader wavefronts: 128 rows x 64 features = 1024 16-byte vectors per feature block;
+    // rows past S are clamped (never used), features past M read the row start (zero weights)
+    const int lt = tid - 64 * NW, lrow = lt >> 3, lvec = lt & 7;   // rows lrow + 32 i
+    const bf16_t* xrow[AV];
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int s = pr * 128 + lrow + 32 * i;
+      s = s < S ? s : S - 1;
+      xrow[i] = x + ((size_t)g * S + s) * M;
+    }
+    u32x4_t areg[RD][AV];
+#define MOE_GATE_LOAD_A(P, kb)                                                           \
+  _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                       \
+    const int kbc_ = (kb) < KB ? (kb) : KB - 1;                                          \
+    const int col_ = kbc_ * 64 + lvec * 8;                                               \
+    areg[P][i] = *reinterpret_cast<const u32x4_t*>(xrow[i] + (col_ < M ? col_ : 0));     \
+  }
+#define MOE_GATE_STORE_A(P, buf)                                                         \
+  _Pragma("unroll") for (int i = 0; i < AV; ++i)                                         \
+    *reinterpret_cast<u32x4_t*>(As + (buf) * 128 * kAPitch + (lrow + 32 * i) * kAPitch + lvec * 8) = areg[P][i];
+    MOE_GATE_LOAD_A(0, 0)
+#pragma unroll
+    for (int p = 1; p < RD; ++p) MOE_GATE_LOAD_A(p, p)
+    MOE_GATE_STORE_A(0, 0)
+    __syncthreads();
+    for (int kb0 = 0; kb0 < KB; kb0 += RD) {
+#pragma unroll
+      for (int q = 0; q < RD; ++q) {
+        if (kb0 + q < KB) {                            // block-uniform
+          // block kb0+q is being multiplied from stage q&1: its ring slot is free again, and
+          // block kb0+q+1 (a clamped copy at the end) goes into the other stage
+          MOE_GATE_LOAD_A(q, kb0 + q + RD)
+          MOE_GATE_STORE_A((q + 1) % RD, (q + 1) & 1)
+          __syncthreads();
+        }
+      }
+    }
+#undef MOE_GATE_LOAD_A
+#undef MOE_GATE_STORE_A
+  } else {
+    // ---- multiplying wavefronts: B operand of MFMA step ks (= 4 kb + j), column tile t, split
+    // sp: ring of four register sets, slot ks & 3, filled PB steps ahead of its use
+    const u32x4_t* bbase = reinterpret_cast<const u32x4_t*>(wgP) + (size_t)wave * ETW * 3 * 64 + lane;
+    const int KS = 4 * KB;
+    u32x4_t bq[4][ETW * 3];
+#define MOE_GATE_LOAD_B(P, ks)                                                           \
+  {                                                                                      \
+    const int ksc_ = (ks) < KS ? (ks) : KS - 1;                                          \
+    _Pragma("unroll") for (int q = 0; q < ETW * 3; ++q)                                  \
+      bq[P][q] = bbase[((size_t)ksc_ * T * 3 + q) * 64];                                 \
+  }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) MOE_GATE_LOAD_B(p, p)
+    __syncthreads();
+    for (int kb = 0; kb < KB; ++kb) {
+      const bf16_t* as = As + (kb & 1) * 128 * kAPitch + r * kAPitch + 32 * h;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        MOE_GATE_LOAD_B((j + PB) & 3, kb * 4 + j + PB)
+        u32x4_t af[4];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+          af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
+#pragma unroll
+        for (int t = 0; t < ETW; ++t)
+#pragma unroll
+          for (int rt = 0; rt < 4; ++rt) {
+            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 2], acc[rt][t]);
+            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 1], acc[rt][t]);
+            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 0], acc[rt][t]);
+          }
+      }
+      __syncthreads();
+    }
+#undef MOE_GATE_LOAD_B
+  }
+  // the A stages are dead from here on; the same LDS holds one chunk of logits at a time
+#pragma unroll 1
+  for (int c = 0; c < 2; ++c) {
+    const int ch = pr * 2 + c;
+    if (ch >= nch) break;                              // block-uniform
+    if (wave < NW) {
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+        for (int t = 0; t < ETW; ++t)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
+                c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
+    }
+    __syncthreads();
+    gate_chunk_epilogue<NT>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+                            hist1, hist2, msum, hh, hh + Epad);
+  }
+}
 #undef MOE_GATE_MFMA
 
 // One block per (group, 32 experts); thread (e, k) owns expert e and the k-th of 8
@@ -798,8 +935,8 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
       if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, lds1, st, MOE_GATE_ARGS);
       else hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, lds2, st, MOE_GATE_ARGS);
     }
-    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_kernel<1, 4, 3>), grid, block, 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 4, 2>), grid, block, 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 3>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<2, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
     else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
 #undef MOE_GATE_ARGS
     rc = check_launch();
