@@ -177,3 +177,48 @@ def test_argument_errors_enqueue_nothing():
     assert ei.value.status == -1
     torch.cuda.synchronize()
     assert (y == 0).all()
+
+
+def test_expert_parallel_layout_on_one_gpu():
+    """The D-device deployment of Section 3 (groups sharded before the experts, experts
+    sharded inside, one exchange each way) replayed on one GPU with the staged entry points:
+    every "device" gates and dispatches its own groups over ALL experts, the exchange is a
+    tensor permutation, every device runs its E/D experts on the rows of all groups, the
+    reverse exchange, and each device combines its own tokens.  Rows are independent in
+    every stage, so the result equals the single-device layer bit for bit."""
+    cfg = next(c for c in SMALL_CASES if c.name == "small")          # G=4, E=16
+    D = 4
+    inp = make_inputs(cfg, device=DEV)
+    y_ref, aux_ref = gpu_forward(cfg, inp)
+    Gl, El = cfg.G // D, cfg.E // D
+    dt = shape_of(cfg).torch_dtype
+    sh_tok = moe.MoEShape(Gl, cfg.S, cfg.M, cfg.H, cfg.E, cfg.C, cfg.act_dtype)    # a device's tokens, all experts
+    sh_exp = moe.MoEShape(cfg.G, cfg.S, cfg.M, cfg.H, El, cfg.C, cfg.act_dtype)    # a device's experts, all groups
+    routes, bufs = [], []
+    for d in range(D):
+        xs, us = inp.x[d * Gl:(d + 1) * Gl].contiguous(), inp.u[d * Gl:(d + 1) * Gl].contiguous()
+        sub = cfg.with_(G=Gl)
+        r = gpu_gate(sub, xs, inp.wg, us, want_gates=False)
+        buf = torch.empty((cfg.E, Gl, cfg.C, cfg.M), dtype=dt, device=DEV)
+        moe.moe_dispatch(sh_tok, xs, r["src_token"], buf)
+        routes.append(r)
+        bufs.append(buf)
+    # exchange: device d receives expert block d of every device's buffer -> [El, G, C, M]
+    outs = []
+    for d in range(D):
+        recv = torch.cat([b[d * El:(d + 1) * El] for b in bufs], dim=1).contiguous()
+        h = torch.empty((El, cfg.G, cfg.C, cfg.H), dtype=dt, device=DEV)
+        out = torch.empty((El, cfg.G, cfg.C, cfg.M), dtype=dt, device=DEV)
+        moe.moe_expert_ffn(sh_exp, recv, inp.wi[d * El:(d + 1) * El].contiguous(),
+                           inp.wo[d * El:(d + 1) * El].contiguous(), h, out)
+        outs.append(out)
+    # reverse exchange and combine
+    full = torch.cat(outs, dim=0)                                     # [E, G, C, M]
+    for d in range(D):
+        mine = full[:, d * Gl:(d + 1) * Gl].contiguous()
+        y = torch.empty((Gl, cfg.S, cfg.M), dtype=dt, device=DEV)
+        r = routes[d]
+        moe.moe_combine(sh_tok, mine, r["expert_idx"], r["slot"], r["weight"], y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_ref[d * Gl:(d + 1) * Gl])
+        assert torch.equal(r["aux"], aux_ref[d * Gl:(d + 1) * Gl])
