@@ -104,6 +104,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="paper")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="also time the forward as replays of one captured HIP graph (reported as "
+                         "an extra field; the metric itself is always the eager call sequence)")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the extra (untimed for the metric) measurement of the backward pass")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -207,6 +210,18 @@ def main():
         "ffn_mfma_frac": 2 * flops_launch / ((stage_ms["expert_gemm1"] + stage_ms["expert_gemm2"]) * 1e-3)
                          / 1e12 / peak,
     }
+    if args.hip_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+        for _ in range(W):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["hip_graph_ms_per_step"] = (time.perf_counter() - g0) * 1e3 / K
     if not args.no_backward:
         out["backward"] = time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak)
     if not args.no_cpu_baseline:

@@ -222,3 +222,50 @@ def test_expert_parallel_layout_on_one_gpu():
         torch.cuda.synchronize()
         assert torch.equal(y, y_ref[d * Gl:(d + 1) * Gl])
         assert torch.equal(r["aux"], aux_ref[d * Gl:(d + 1) * Gl])
+
+
+def test_forward_and_backward_replay_from_a_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no
+    synchronisation, no memset nodes), so a layer step can be captured once and replayed.
+    Replays with fresh inputs in the captured buffers must equal eager calls bit for bit,
+    on every replay (eager work and synchronisations in between)."""
+    from harness import gpu_forward_backward
+    from workloads import make_upstream
+    cfg = next(c for c in SMALL_CASES if c.name == "small")
+    sh = shape_of(cfg)
+    inputs = [make_inputs(cfg.with_(seed=cfg.seed + k), device=DEV) for k in range(3)]
+    ups = [make_upstream(cfg.with_(seed=cfg.seed + k), device=DEV) for k in range(3)]
+    st = inputs[0]
+    x, wg, u = st.x.clone(), st.wg.clone(), st.u.clone()
+    wi, wo = st.wi.clone(), st.wo.clone()
+    dy, daux = ups[0][0].clone(), ups[0][1].clone()
+    y = torch.empty_like(x)
+    aux = torch.empty(cfg.G, dtype=torch.float32, device=DEV)
+    dx, dwg, dwi, dwo = torch.empty_like(x), torch.empty_like(wg), torch.empty_like(wi), torch.empty_like(wo)
+    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+
+    def step():
+        moe.moe_forward_train(sh, x, wg, u, wi, wo, y, aux, fws)
+        moe.moe_backward(sh, x, wg, wi, wo, dy, daux, fws, dx, dwg, dwi, dwo, bws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                        # first call outside capture: one-time kernel attributes
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for k in (1, 2, 0, 1):
+        inp, (dyk, dauxk) = inputs[k], ups[k]
+        x.copy_(inp.x); wg.copy_(inp.wg); u.copy_(inp.u); wi.copy_(inp.wi); wo.copy_(inp.wo)
+        dy.copy_(dyk); daux.copy_(dauxk)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {"y": y.clone(), "aux": aux.clone(), "dx": dx.clone(), "dwg": dwg.clone(),
+               "dwi": dwi.clone(), "dwo": dwo.clone()}
+        want = gpu_forward_backward(cfg, inp, dyk, dauxk)            # eager, own buffers
+        for name in got:
+            assert torch.equal(got[name], want[name]), (k, name)
