@@ -61,6 +61,47 @@ def cpu_baseline(cfg, inp, seconds_hint=20.0):
                       f"fp64 numpy, {t_total:.1f} s; includes widening each expert's weights to fp64"}
 
 
+def yardsticks(cfg, dev):
+    """Context for the roofline fractions, measured in the same process on the same box: a
+    plain device copy, the vendor library's square bf16 GEMM and its batched GEMMs of exactly
+    the two expert-GEMM shapes (torch.bmm, random operands).  Not part of any product path."""
+    import torch
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    out["device_copy_TBps"] = 2 * src.numel() / (timed(lambda: dst.copy_(src), 5) * 1e-3) / 1e12
+    del src, dst
+    if cfg.act_dtype == "bf16":
+        a = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+        b = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+        out["vendor_gemm_8192_cubed_TFLOPs"] = 2 * 8192 ** 3 / (timed(lambda: a @ b, 5) * 1e-3) / 1e12
+        del a, b
+        rows = cfg.G * cfg.C
+        if cfg.E * (rows * cfg.H + cfg.M * cfg.H) * 2 < 40e9:       # operands within 40 GB
+            a1 = torch.randn(cfg.E, rows, cfg.M, device=dev, dtype=torch.bfloat16)
+            b1 = torch.randn(cfg.E, cfg.M, cfg.H, device=dev, dtype=torch.bfloat16)
+            out["vendor_bmm_gemm1_shape_ms"] = timed(lambda: torch.bmm(a1, b1), 5)
+            a2 = torch.bmm(a1, b1).relu_()
+            del a1, b1
+            b2 = torch.randn(cfg.E, cfg.H, cfg.M, device=dev, dtype=torch.bfloat16)
+            out["vendor_bmm_gemm2_shape_ms"] = timed(lambda: torch.bmm(a2, b2), 5)
+            del a2, b2
+    torch.cuda.empty_cache()
+    return out
+
+
 def time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak):
     """Backward pass of the same layer (not part of `value`): K calls of moe_backward_events
     after one moe_forward_train, stage times from HIP events on the kernels' stream."""
@@ -107,6 +148,8 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="also time the forward as replays of one captured HIP graph (reported as "
                          "an extra field; the metric itself is always the eager call sequence)")
+    ap.add_argument("--no-yardsticks", action="store_true",
+                    help="skip the copy / vendor-GEMM context measurements")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the extra (untimed for the metric) measurement of the backward pass")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -222,6 +265,8 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         out["hip_graph_ms_per_step"] = (time.perf_counter() - g0) * 1e3 / K
+    if not args.no_yardsticks:
+        out["yardsticks"] = yardsticks(cfg, dev)
     if not args.no_backward:
         out["backward"] = time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak)
     if not args.no_cpu_baseline:
