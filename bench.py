@@ -26,10 +26,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM-side bytes per launch of the expert GEMMs on the `paper` workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come
-# from a plain 1 GiB copy in the same runs).  Summary: profiles/moe_forward_paper_hbm_traffic.md
+# from a plain 1 GiB copy in the same runs).  Summary: profiles/moe_layer_paper_hbm_traffic.md
 MEASURED_TRAFFIC_BYTES = {
-    "paper": {"expert_gemm1": (854100 * 2.0 + 1048600) * 1024,
-              "expert_gemm2": (789600 * 2.0 + 131070) * 1024},
+    "paper": {"expert_gemm1": (804372 * 2.0 + 1048576) * 1024,
+              "expert_gemm2": (789628 * 2.0 + 131072) * 1024},
 }
 
 
