@@ -230,6 +230,69 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
                         void* dx, float* dwg, void* dwi, void* dwo,
                         void* ws, size_t ws_bytes, void* stream, void* const* events);
 
+/*
+ * ---- The encoder layers around the MoE layer ---------------------------------------
+ * Section 2.1: an encoder layer is a self-attention layer followed by a position-wise
+ * feed-forward layer, with residual connections and layer normalisation; the MoE
+ * Transformer replaces every other feed-forward layer by the MoE layer.  Model sizes of the
+ * paper (Appendix, "Machine Translation Experiments Details"): M = 1024, H = 8192, 16 heads
+ * of key/value dimension 128.  The entry points below evaluate (forward) one dense and one
+ * MoE encoder layer,
+ *     a = x + Attention_1(LN_1(x))      b = a + FFN(LN_2(a))
+ *     c = b + Attention_2(LN_3(b))      y = c + MoE(LN_4(c))
+ * with: layer normalisation first in every sub-layer (the paper does not fix the order),
+ * LN(v) = gamma (v - mean) / sqrt(var + 1e-6) + beta over M (population variance);
+ * Attention(u) = concat_h softmax(Q_h K_h^T / sqrt(d)) V_h . wo with [Q|K|V] = u . wqkv,
+ * no biases, no mask (all sequences have length L), no dropout; FFN(u) = relu(u w1) w2.
+ * Tokens are the rows of a [B, L, M] batch and, unchanged in order, the [G, S, M] tokens of
+ * the MoE layer (B*L == G*S).  Element types as everywhere: activations and weight matrices
+ * cfg->act_dtype, LN parameters and the gate fp32; fp32 accumulation; every stored
+ * intermediate is rounded once.
+ */
+typedef struct {
+  int32_t B, L;      /* sequences and their length; B*L == cfg->G * cfg->S */
+  int32_t heads, d;  /* attention heads and key/value dimension; A = heads*d */
+} moe_encoder_dims;
+
+typedef struct {       /* device pointers, owned by the caller */
+  const float *ln_gamma[4], *ln_beta[4]; /* [M] each, sub-layers in the order of the formulas */
+  const void *wqkv[2];                   /* [M, 3A]: columns [0,A) = Wq, [A,2A) = Wk, [2A,3A) = Wv */
+  const void *wo_att[2];                 /* [A, M] */
+  const void *w1, *w2;                   /* dense feed-forward layer: [M,H], [H,M] */
+  const float *wg;                       /* MoE layer, as in moe_forward */
+  const void *wi, *wo;
+} moe_encoder_weights;
+
+/* s = x + delta (delta may be NULL: then s = x and sum_out is not written) and
+ * n = LN(s), rows = G*S.  in: x, delta [G,S,M]; gamma, beta [M] fp32
+ * out: sum_out [G,S,M] (NULL allowed when delta is NULL); norm_out [G,S,M]. */
+int moe_add_layer_norm(const moe_config* cfg, const void* x, const void* delta,
+                       const float* gamma, const float* beta, void* sum_out, void* norm_out,
+                       void* stream);
+
+/* Bytes of workspace of moe_self_attention / moe_encoder_pair_forward.  Pure host functions. */
+int moe_attention_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes);
+int moe_encoder_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes);
+
+/* out = Attention(u) (no residual): u [B,L,M], wqkv [M,3A], wo_att [A,M] -> out [B,L,M].
+ * The flash-style MFMA kernel serves bf16 with d in {64,128} and L % 128 == 0; other
+ * shapes use a plain kernel that needs (L + d) * 16 bytes of LDS <= 64 KB. */
+int moe_self_attention(const moe_config* cfg, const moe_encoder_dims* dims, const void* u,
+                       const void* wqkv, const void* wo_att, void* out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* out = relu(u w1) w2: u [G,S,M], w1 [M,H], w2 [H,M]; h_ws [G,S,H] scratch. */
+int moe_dense_ffn(const moe_config* cfg, const void* u, const void* w1, const void* w2,
+                  void* h_ws, void* out, void* stream);
+
+/* The two encoder layers of the formulas above.  in: x [B,L,M], weights, u [G,S] (uniforms of
+ * the MoE layer's random routing).  out: y [B,L,M], aux [G].  ws >= moe_encoder_workspace_bytes,
+ * 256-byte aligned.  Exactly the sequence moe_add_layer_norm, moe_self_attention,
+ * moe_dense_ffn, moe_forward, with the residual sums in between. */
+int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                             const moe_encoder_weights* w, const float* u, void* y, float* aux,
+                             void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,13 +5,17 @@
 ``libmoe_gfx950.so`` (built by ``python -m paper_2006_16668_amd.build``).
 There is no CPU fallback: a missing library raises on first use.
 """
-from .binding import (moe_backward, moe_backward_events, moe_backward_workspace_bytes,
+from .binding import (EncoderDims, moe_add_layer_norm, moe_attention_workspace_bytes,
+                      moe_dense_ffn, moe_encoder_pair_forward, moe_encoder_workspace_bytes,
+                      moe_self_attention, moe_backward, moe_backward_events, moe_backward_workspace_bytes,
                       moe_forward_train, MoEError, MoEShape, library_path, load_library, moe_combine, moe_dispatch,
                       moe_expert_ffn, moe_forward, moe_forward_events, moe_forward_fuses_dispatch,
                       moe_gate, moe_gate_workspace_bytes,
                       moe_status_string, moe_workspace_bytes)
 
-__all__ = ["moe_backward", "moe_backward_events", "moe_backward_workspace_bytes",
+__all__ = ["EncoderDims", "moe_add_layer_norm", "moe_attention_workspace_bytes", "moe_dense_ffn",
+           "moe_encoder_pair_forward", "moe_encoder_workspace_bytes", "moe_self_attention",
+           "moe_backward", "moe_backward_events", "moe_backward_workspace_bytes",
            "moe_forward_train", "MoEError", "MoEShape", "library_path", "load_library", "moe_combine", "moe_dispatch",
            "moe_expert_ffn", "moe_forward", "moe_forward_events", "moe_forward_fuses_dispatch",
            "moe_gate", "moe_gate_workspace_bytes",

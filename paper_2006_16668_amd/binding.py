@@ -23,7 +23,9 @@ SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
            "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
            "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
-           "moe_backward", "moe_backward_events")
+           "moe_backward", "moe_backward_events", "moe_add_layer_norm",
+           "moe_attention_workspace_bytes", "moe_encoder_workspace_bytes", "moe_self_attention",
+           "moe_dense_ffn", "moe_encoder_pair_forward")
 FORWARD_EVENTS = 6
 BACKWARD_EVENTS = 8
 
@@ -36,6 +38,29 @@ class MoEError(RuntimeError):
 
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("G", "S", "M", "H", "E", "C", "act_dtype")]
+
+
+class _EncoderDims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "L", "heads", "d")]
+
+
+class _EncoderWeights(ctypes.Structure):
+    _fields_ = [("ln_gamma", ctypes.c_void_p * 4), ("ln_beta", ctypes.c_void_p * 4),
+                ("wqkv", ctypes.c_void_p * 2), ("wo_att", ctypes.c_void_p * 2),
+                ("w1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("wg", ctypes.c_void_p),
+                ("wi", ctypes.c_void_p), ("wo", ctypes.c_void_p)]
+
+
+@dataclass(frozen=True)
+class EncoderDims:
+    """B sequences of length L (B*L == G*S), attention heads and key/value dimension d."""
+    B: int
+    L: int
+    heads: int
+    d: int
+
+    def _c(self):
+        return _EncoderDims(self.B, self.L, self.heads, self.d)
 
 
 @dataclass(frozen=True)
@@ -88,6 +113,13 @@ def load_library() -> ctypes.CDLL:
         "moe_forward_events": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                ctypes.POINTER(ctypes.c_void_p)],
         "moe_forward_train": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "moe_add_layer_norm": [cfgp, vp, vp, vp, vp, vp, vp, vp],
+        "moe_attention_workspace_bytes": [cfgp, ctypes.POINTER(_EncoderDims), ctypes.POINTER(sz)],
+        "moe_encoder_workspace_bytes": [cfgp, ctypes.POINTER(_EncoderDims), ctypes.POINTER(sz)],
+        "moe_self_attention": [cfgp, ctypes.POINTER(_EncoderDims), vp, vp, vp, vp, vp, sz, vp],
+        "moe_dense_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
+        "moe_encoder_pair_forward": [cfgp, ctypes.POINTER(_EncoderDims), vp,
+                                     ctypes.POINTER(_EncoderWeights), vp, vp, vp, vp, sz, vp],
         "moe_backward_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_backward": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp],
         "moe_backward_events": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp,
@@ -283,3 +315,77 @@ def moe_backward_events(shape: MoEShape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dw
     _check(load_library().moe_backward_events(
         ctypes.byref(c), *_backward_args(shape, x, wg, wi, wo, dy, daux, fwd_ws, dx, dwg, dwi, dwo, ws),
         handles), "moe_backward_events")
+
+
+# ---- encoder layers around the MoE layer
+def moe_add_layer_norm(shape: MoEShape, x, delta, gamma, beta, sum_out, norm_out):
+    G, S, M = shape.G, shape.S, shape.M
+    dt, f32 = shape.torch_dtype, torch.float32
+    c = shape._c()
+    _check(load_library().moe_add_layer_norm(
+        ctypes.byref(c), _ptr(x, dt, (G, S, M), "x"), _ptr(delta, dt, (G, S, M), "delta"),
+        _ptr(gamma, f32, (M,), "gamma"), _ptr(beta, f32, (M,), "beta"),
+        _ptr(sum_out, dt, (G, S, M), "sum_out"), _ptr(norm_out, dt, (G, S, M), "norm_out"), _stream()),
+        "moe_add_layer_norm")
+
+
+def _ws_query(fn_name, shape: MoEShape, dims: EncoderDims) -> int:
+    n = ctypes.c_size_t(0)
+    c, d = shape._c(), dims._c()
+    _check(getattr(load_library(), fn_name)(ctypes.byref(c), ctypes.byref(d), ctypes.byref(n)), fn_name)
+    return n.value
+
+
+def moe_attention_workspace_bytes(shape: MoEShape, dims: EncoderDims) -> int:
+    return _ws_query("moe_attention_workspace_bytes", shape, dims)
+
+
+def moe_encoder_workspace_bytes(shape: MoEShape, dims: EncoderDims) -> int:
+    return _ws_query("moe_encoder_workspace_bytes", shape, dims)
+
+
+def moe_self_attention(shape: MoEShape, dims: EncoderDims, u, wqkv, wo_att, out, ws):
+    G, S, M = shape.G, shape.S, shape.M
+    A = dims.heads * dims.d
+    dt = shape.torch_dtype
+    c, d = shape._c(), dims._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_self_attention(
+        ctypes.byref(c), ctypes.byref(d), _ptr(u, dt, (G, S, M), "u"), _ptr(wqkv, dt, (M, 3 * A), "wqkv"),
+        _ptr(wo_att, dt, (A, M), "wo_att"), _ptr(out, dt, (G, S, M), "out"), wsp, wsn, _stream()),
+        "moe_self_attention")
+
+
+def moe_dense_ffn(shape: MoEShape, u, w1, w2, h_ws, out):
+    G, S, M, H = shape.G, shape.S, shape.M, shape.H
+    dt = shape.torch_dtype
+    c = shape._c()
+    _check(load_library().moe_dense_ffn(
+        ctypes.byref(c), _ptr(u, dt, (G, S, M), "u"), _ptr(w1, dt, (M, H), "w1"), _ptr(w2, dt, (H, M), "w2"),
+        _ptr(h_ws, dt, (G, S, H), "h_ws"), _ptr(out, dt, (G, S, M), "out"), _stream()), "moe_dense_ffn")
+
+
+def moe_encoder_pair_forward(shape: MoEShape, dims: EncoderDims, x, weights: dict, u, y, aux, ws):
+    """weights: ln_gamma / ln_beta (4 tensors [M] fp32 each), wqkv / wo_att (2 each), w1, w2,
+    wg, wi, wo."""
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    A = dims.heads * dims.d
+    dt, f32 = shape.torch_dtype, torch.float32
+    w = _EncoderWeights()
+    for i in range(4):
+        w.ln_gamma[i] = _ptr(weights["ln_gamma"][i], f32, (M,), "ln_gamma").value
+        w.ln_beta[i] = _ptr(weights["ln_beta"][i], f32, (M,), "ln_beta").value
+    for i in range(2):
+        w.wqkv[i] = _ptr(weights["wqkv"][i], dt, (M, 3 * A), "wqkv").value
+        w.wo_att[i] = _ptr(weights["wo_att"][i], dt, (A, M), "wo_att").value
+    w.w1 = _ptr(weights["w1"], dt, (M, H), "w1").value
+    w.w2 = _ptr(weights["w2"], dt, (H, M), "w2").value
+    w.wg = _ptr(weights["wg"], f32, (M, E), "wg").value
+    w.wi = _ptr(weights["wi"], dt, (E, M, H), "wi").value
+    w.wo = _ptr(weights["wo"], dt, (E, H, M), "wo").value
+    c, d = shape._c(), dims._c()
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_encoder_pair_forward(
+        ctypes.byref(c), ctypes.byref(d), _ptr(x, dt, (G, S, M), "x"), ctypes.byref(w),
+        _ptr(u, f32, (G, S), "u"), _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"),
+        wsp, wsn, _stream()), "moe_encoder_pair_forward")

@@ -129,6 +129,75 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   return mark(5) ? MOE_OK : MOE_EHIP;
 }
 
+// ---- encoder layers: C[rows,N] = A[rows,K] . B[K,N] (optionally relu) through the expert GEMM
+// launchers with a one-expert configuration
+int dense_gemm(const moe_config& c, long long rows, int K, int N, bool relu, const void* A,
+               const void* B, void* Cout, hipStream_t st) {
+  if (rows > 0x7fffffffLL) return MOE_EUNSUPPORTED;
+  moe_config g = c;
+  g.E = 1;
+  g.G = 1;
+  g.C = (int)rows;
+  if (relu) {                       // h = relu(buf . wi): buf [rows, M:=K], wi [K, H:=N]
+    g.M = K;
+    g.H = N;
+    return moe::launch_expert_gemm1(g, A, B, Cout, st);
+  }
+  g.M = N;                          // out = h . wo: h [rows, H:=K], wo [K, M:=N]
+  g.H = K;
+  return moe::launch_expert_gemm2(g, A, B, Cout, st);
+}
+
+int check_dims(const moe_config* cfg, const moe_encoder_dims* d) {
+  if (d == nullptr) return MOE_EINVAL;
+  if (d->B < 1 || d->L < 1 || d->heads < 1 || d->d < 1) return MOE_EINVAL;
+  if ((long long)d->B * d->L != (long long)cfg->G * cfg->S) return MOE_EINVAL;
+  if (d->d % 8 != 0 || (long long)d->heads * d->d > 0x7fffffLL) return MOE_EUNSUPPORTED;
+  return MOE_OK;
+}
+
+struct AttentionWs { size_t qkv, ctx, total; };
+AttentionWs carve_att(const moe_config& c, const moe_encoder_dims& d) {
+  const size_t N = (size_t)c.G * c.S, A = (size_t)d.heads * d.d;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  AttentionWs w{};
+  w.qkv = 0;
+  w.ctx = align_up(N * 3 * A * elt, 256);
+  w.total = w.ctx + align_up(N * A * elt, 256);
+  return w;
+}
+
+struct EncoderWs { size_t norm, sub, a, b, c, hden, att, moe, total; };
+EncoderWs carve_enc(const moe_config& c, const moe_encoder_dims& d) {
+  const size_t N = (size_t)c.G * c.S;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  EncoderWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.norm = take(N * c.M * elt);
+  w.sub = take(N * c.M * elt);
+  w.a = take(N * c.M * elt);
+  w.b = take(N * c.M * elt);
+  w.c = take(N * c.M * elt);
+  w.hden = take(N * c.H * elt);
+  w.att = take(carve_att(c, d).total);
+  w.moe = take(carve(c).total);
+  w.total = off;
+  return w;
+}
+
+int attention_impl(const moe_config& c, const moe_encoder_dims& d, const void* u, const void* wqkv,
+                   const void* wo_att, void* out, char* ws, hipStream_t st) {
+  const AttentionWs w = carve_att(c, d);
+  const long long N = (long long)c.G * c.S;
+  const int A = d.heads * d.d;
+  int rc = dense_gemm(c, N, c.M, 3 * A, false, u, wqkv, ws + w.qkv, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_attention_core(c.act_dtype, ws + w.qkv, ws + w.ctx, d.B, d.L, d.heads, d.d, st);
+  if (rc != MOE_OK) return rc;
+  return dense_gemm(c, N, A, c.M, false, ws + w.ctx, wo_att, out, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -314,6 +383,111 @@ int moe_forward(const moe_config* cfg, const void* x, const float* wg, const flo
                 const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
                 void* stream) {
   return moe_forward_events(cfg, x, wg, u, wi, wo, y, aux, ws, ws_bytes, stream, nullptr);
+}
+
+int moe_add_layer_norm(const moe_config* cfg, const void* x, const void* delta, const float* gamma,
+                       const float* beta, void* sum_out, void* norm_out, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, gamma, beta, norm_out};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if (delta != nullptr && (sum_out == nullptr || !aligned16(delta) || !aligned16(sum_out)))
+    return MOE_EINVAL;
+  return moe::launch_add_layer_norm(cfg->act_dtype, x, delta, gamma, beta, sum_out, norm_out,
+                                    (long long)cfg->G * cfg->S, cfg->M,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int moe_attention_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve_att(*cfg, *dims).total;
+  return MOE_OK;
+}
+
+int moe_encoder_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve_enc(*cfg, *dims).total;
+  return MOE_OK;
+}
+
+int moe_self_attention(const moe_config* cfg, const moe_encoder_dims* dims, const void* u,
+                       const void* wqkv, const void* wo_att, void* out, void* ws, size_t ws_bytes,
+                       void* stream) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  const void* req[] = {u, wqkv, wo_att, out, ws};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  if (ws_bytes < carve_att(*cfg, *dims).total) return MOE_EWORKSPACE;
+  return attention_impl(*cfg, *dims, u, wqkv, wo_att, out, static_cast<char*>(ws),
+                        static_cast<hipStream_t>(stream));
+}
+
+int moe_dense_ffn(const moe_config* cfg, const void* u, const void* w1, const void* w2, void* h_ws,
+                  void* out, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {u, w1, w2, h_ws, out};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long long N = (long long)cfg->G * cfg->S;
+  const int rc1 = dense_gemm(*cfg, N, cfg->M, cfg->H, true, u, w1, h_ws, st);
+  if (rc1 != MOE_OK) return rc1;
+  return dense_gemm(*cfg, N, cfg->H, cfg->M, false, h_ws, w2, out, st);
+}
+
+int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                             const moe_encoder_weights* w, const float* u, void* y, float* aux,
+                             void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (w == nullptr) return MOE_EINVAL;
+  const void* req[] = {x, u, y, aux, ws, w->wqkv[0], w->wqkv[1], w->wo_att[0], w->wo_att[1], w->w1,
+                       w->w2, w->wg, w->wi, w->wo, w->ln_gamma[0], w->ln_gamma[1], w->ln_gamma[2],
+                       w->ln_gamma[3], w->ln_beta[0], w->ln_beta[1], w->ln_beta[2], w->ln_beta[3]};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  const EncoderWs e = carve_enc(*cfg, *dims);
+  if (ws_bytes < e.total) return MOE_EWORKSPACE;
+  char* base = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long long N = (long long)cfg->G * cfg->S;
+  const int dt = cfg->act_dtype;
+  void *norm = base + e.norm, *sub = base + e.sub, *a = base + e.a, *b = base + e.b, *c = base + e.c;
+  // layer 1: a = x + Attention_1(LN_1(x)); b = a + FFN(LN_2(a))
+  rc = moe::launch_add_layer_norm(dt, x, nullptr, w->ln_gamma[0], w->ln_beta[0], nullptr, norm, N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = attention_impl(*cfg, *dims, norm, w->wqkv[0], w->wo_att[0], sub, base + e.att, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_add_layer_norm(dt, x, sub, w->ln_gamma[1], w->ln_beta[1], a, norm, N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = dense_gemm(*cfg, N, cfg->M, cfg->H, true, norm, w->w1, base + e.hden, st);
+  if (rc != MOE_OK) return rc;
+  rc = dense_gemm(*cfg, N, cfg->H, cfg->M, false, base + e.hden, w->w2, sub, st);
+  if (rc != MOE_OK) return rc;
+  // layer 2: c = b + Attention_2(LN_3(b)); y = c + MoE(LN_4(c))
+  rc = moe::launch_add_layer_norm(dt, a, sub, w->ln_gamma[2], w->ln_beta[2], b, norm, N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = attention_impl(*cfg, *dims, norm, w->wqkv[1], w->wo_att[1], sub, base + e.att, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_add_layer_norm(dt, b, sub, w->ln_gamma[3], w->ln_beta[3], c, norm, N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = forward_impl(cfg, norm, w->wg, u, w->wi, w->wo, sub, aux, base + e.moe, carve(*cfg).total,
+                    stream, nullptr, false);
+  if (rc != MOE_OK) return rc;
+  return moe::launch_add_rows(dt, c, sub, y, N * cfg->M, st);
 }
 
 }  // extern "C"

@@ -383,10 +383,10 @@ GateBwdPlan gate_bwd_plan(const moe_config& c) {
   if (p.mfma) {
     p.cols = (int)cols;
     // token ranges (a power of two of them, each a multiple of 32 tokens and at least 128)
-    // so that there are a few hundred 256x256 tiles to spread over the compute units
+    // so that there is about one 256x256 tile per compute unit
     const long long tiles = (long long)(c.M / 256) * (cols / 256);
     int s = 1;
-    while ((long long)s * 2 * tiles <= 512 && (tokens / 32) % (s * 2) == 0 && tokens / (s * 2) >= 128)
+    while ((long long)s * 2 * tiles <= 256 && (tokens / 32) % (s * 2) == 0 && tokens / (s * 2) >= 128)
       s *= 2;
     p.splits = s;
     p.dzp_bytes = (size_t)tokens * cols * 2;

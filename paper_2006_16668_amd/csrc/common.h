@@ -165,6 +165,15 @@ bool gemm_bf16_f32out_ok(int R, int N, int K);
 int launch_gemm_bf16_f32out(bool transposed_a, const void* A, const void* B, float* Cout,
                             int batch, int R, int N, int K, hipStream_t st);
 
+// Transformer encoder sub-layers around the MoE layer (encoder.hip)
+int launch_add_layer_norm(int act_dtype, const void* x, const void* delta, const float* gamma,
+                          const float* beta, void* sum_out, void* norm_out, long long rows, int M,
+                          hipStream_t st);
+int launch_add_rows(int act_dtype, const void* a, const void* b, void* y, long long elems,
+                    hipStream_t st);
+int launch_attention_core(int act_dtype, const void* qkv, void* ctx, long long B, int L, int heads,
+                          int d, hipStream_t st);
+
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 
 }  // namespace moe

@@ -163,3 +163,25 @@ def make_upstream(cfg: MoEConfig, device="cpu"):
     dy = _randn((cfg.G, cfg.S, cfg.M), gen, device).to(_TORCH_DTYPE[cfg.act_dtype])
     daux = _randn((cfg.G,), gen, device)
     return dy, daux
+
+
+def make_encoder_weights(cfg: MoEConfig, heads: int, d: int, device="cpu"):
+    """Weights of the two encoder layers around the MoE layer (all but the MoE layer's own):
+    layer-norm gains 1 + 0.1 N(0,1) and offsets 0.1 N(0,1) in fp32; attention and dense
+    feed-forward matrices N(0, 1/fan_in) rounded to the activation type.  A generator of
+    their own, seeded from cfg.seed."""
+    device = torch.device(device)
+    dt = _TORCH_DTYPE[cfg.act_dtype]
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed + 15485863)
+    M, H, A = cfg.M, cfg.H, heads * d
+    w = {"ln_gamma": [], "ln_beta": [], "wqkv": [], "wo_att": []}
+    for _ in range(4):
+        w["ln_gamma"].append(1.0 + 0.1 * _randn((M,), gen, device))
+        w["ln_beta"].append(0.1 * _randn((M,), gen, device))
+    for _ in range(2):
+        w["wqkv"].append((_randn((M, 3 * A), gen, device) / float(np.sqrt(M))).to(dt))
+        w["wo_att"].append((_randn((A, M), gen, device) / float(np.sqrt(A))).to(dt))
+    w["w1"] = (_randn((M, H), gen, device) / float(np.sqrt(M))).to(dt)
+    w["w2"] = (_randn((H, M), gen, device) / float(np.sqrt(H))).to(dt)
+    return w
