@@ -102,6 +102,52 @@ def yardsticks(cfg, dev):
     return out
 
 
+def time_encoder(moe, cfg, sh, inp, K, W, peak):
+    """The two encoder layers around the MoE layer at the paper's attention sizes (16 heads of
+    key/value dimension 128, sequences of 1024 tokens); stage times from separate timed loops
+    of the staged entry points.  Not part of `value`."""
+    import torch
+    from workloads import make_encoder_weights
+    dev = inp.x.device
+    heads, d = 16, 128
+    L = 1024 if cfg.N % 1024 == 0 else cfg.S
+    dims = moe.EncoderDims(cfg.N // L, L, heads, d)
+    A = heads * d
+    w = make_encoder_weights(cfg, heads, d, device=dev)
+    weights = dict(w, wg=inp.wg, wi=inp.wi, wo=inp.wo)
+    y = torch.empty_like(inp.x)
+    t = torch.empty_like(inp.x)
+    aux = torch.empty(cfg.G, dtype=torch.float32, device=dev)
+    ws = torch.empty(moe.moe_encoder_workspace_bytes(sh, dims), dtype=torch.uint8, device=dev)
+    aws = torch.empty(moe.moe_attention_workspace_bytes(sh, dims), dtype=torch.uint8, device=dev)
+    hden = torch.empty((cfg.G, cfg.S, cfg.H), dtype=inp.x.dtype, device=dev)
+
+    def timed(fn):
+        for _ in range(W):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(K):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / K
+
+    pair = timed(lambda: moe.moe_encoder_pair_forward(sh, dims, inp.x, weights, inp.u, y, aux, ws))
+    att = timed(lambda: moe.moe_self_attention(sh, dims, inp.x, w["wqkv"][0], w["wo_att"][0], t, aws))
+    ffn = timed(lambda: moe.moe_dense_ffn(sh, inp.x, w["w1"], w["w2"], hden, t))
+    ln = timed(lambda: moe.moe_add_layer_norm(sh, inp.x, t, w["ln_gamma"][0], w["ln_beta"][0], y, t))
+    att_flops = 2.0 * cfg.N * cfg.M * 3 * A + 2.0 * cfg.N * A * cfg.M + 4.0 * cfg.N * L * A
+    return {"ms_per_step": pair, "tokens_per_s": cfg.N / (pair * 1e-3),
+            "dims": {"sequences": dims.B, "length": L, "heads": heads, "d": d},
+            "self_attention_ms": att, "self_attention_mfma_frac": att_flops / (att * 1e-3) / 1e12 / peak,
+            "dense_ffn_ms": ffn, "dense_ffn_mfma_frac": 4.0 * cfg.N * cfg.M * cfg.H / (ffn * 1e-3) / 1e12 / peak,
+            "add_layer_norm_ms": ln,
+            "add_layer_norm_hbm_frac": 4.0 * cfg.N * cfg.M * inp.x.element_size() / (ln * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "note": "x -> attention + dense FFN layer -> attention + MoE layer (forward); not part of value"}
+
+
 def time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak):
     """Backward pass of the same layer (not part of `value`): K calls of moe_backward_events
     after one moe_forward_train, stage times from HIP events on the kernels' stream."""
@@ -148,6 +194,8 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="also time the forward as replays of one captured HIP graph (reported as "
                          "an extra field; the metric itself is always the eager call sequence)")
+    ap.add_argument("--no-encoder", action="store_true",
+                    help="skip the extra measurement of the encoder layers around the MoE layer")
     ap.add_argument("--no-yardsticks", action="store_true",
                     help="skip the copy / vendor-GEMM context measurements")
     ap.add_argument("--no-backward", action="store_true",
@@ -265,6 +313,8 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         out["hip_graph_ms_per_step"] = (time.perf_counter() - g0) * 1e3 / K
+    if not args.no_encoder and cfg.act_dtype == "bf16":
+        out["encoder_pair"] = time_encoder(moe, cfg, sh, inp, K, W, peak)
     if not args.no_yardsticks:
         out["yardsticks"] = yardsticks(cfg, dev)
     if not args.no_backward:

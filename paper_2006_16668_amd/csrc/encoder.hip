@@ -151,20 +151,21 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
 //         operand, fetched with the transposing LDS read from the V block staged as
 //         [keys][d] with the key rows stored in the matching order (bits 2 and 3 of the key
 //         index swapped inside each 32-key tile).
-// The V block (64 keys x D) is staged through LDS once per block and step, double buffered;
-// K fragments come straight from L2.
+// The K and V blocks (64 keys x D each) are staged through LDS once per block and step, double
+// buffered, the next block waiting in registers while the current one is multiplied.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int D>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
     const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, int L, int heads) {
   constexpr int KS = D / 16;                 // MFMA steps over d for the scores
   constexpr int DT = D / 32;                 // 32-row tiles of O^T
-  constexpr int kVPitch = D * 2 + 16;        // bytes per staged V row (16-byte pad: bank spread)
-  __shared__ __attribute__((aligned(16))) unsigned char vs[2][64 * kVPitch];
+  constexpr int kPitch = D * 2 + 16;         // bytes per staged K / V row (16-byte pad: bank spread)
+  constexpr int kTile = 64 * kPitch;         // one staged block of 64 keys
+  __shared__ __attribute__((aligned(16))) unsigned char kvs[2][2 * kTile];   // stage: K block, V block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hf = lane >> 5;
   const int qblocks = L / 128;
@@ -189,44 +190,51 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[t][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float sl2 = 1.4426950408889634f / sqrtf((float)D);   // scores are kept in log2 units
+  float m_run = -INFINITY, l_run = 0.f;       // running maximum (in log2 units) and sum
+  const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
-  // cooperative V staging: 64 keys x D bf16 = 64 * D / 8 16-byte vectors, 256 threads
-  constexpr int VV = 64 * D / 8 / 256;       // vectors per thread (2 for D = 64, 4 for D = 128)
+  // cooperative staging of a block of 64 keys: K rows as they are, V rows in the order the
+  // P^T operand needs (bits 2 and 3 of the key index swapped); 64 * D / 8 16-byte vectors each.
+  // The block after the current one waits in registers while the current one is multiplied.
+  constexpr int VV = 64 * D / 8 / 256;       // vectors per thread and operand
   constexpr int VPR = D / 8;                 // vectors per row
-  u32x4_t vreg[VV];
-#define MOE_ATT_LOAD_V(kb)                                                                    \
+  u32x4_t kreg[VV], vreg[VV];
+#define MOE_ATT_LOAD_KV(kb)                                                                   \
   _Pragma("unroll") for (int i = 0; i < VV; ++i) {                                            \
     const int f = tid + 256 * i, key = f / VPR, c = f % VPR;                                  \
+    kreg[i] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)((kb) * 64 + key) * ld + 8 * c); \
     vreg[i] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)((kb) * 64 + key) * ld + 8 * c); \
   }
-#define MOE_ATT_STORE_V(stage)                                                                \
+#define MOE_ATT_STORE_KV(stage)                                                               \
   _Pragma("unroll") for (int i = 0; i < VV; ++i) {                                            \
     const int f = tid + 256 * i, key = f / VPR, c = f % VPR;                                  \
     const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1); /* swap bits 2, 3 */   \
-    *reinterpret_cast<u32x4_t*>(&vs[stage][pos * kVPitch + 16 * c]) = vreg[i];                \
+    *reinterpret_cast<u32x4_t*>(&kvs[stage][key * kPitch + 16 * c]) = kreg[i];                \
+    *reinterpret_cast<u32x4_t*>(&kvs[stage][kTile + pos * kPitch + 16 * c]) = vreg[i];        \
   }
   const int nkb = L / 64;
-  MOE_ATT_LOAD_V(0)
-  MOE_ATT_STORE_V(0)
+  MOE_ATT_LOAD_KV(0)
+  MOE_ATT_STORE_KV(0)
   __syncthreads();
 
   typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+  typedef u32x4_t __attribute__((address_space(3))) * lds_u4_ptr;
   typedef unsigned char __attribute__((address_space(3))) * lds_ptr;
-  const uint32_t vs0 = (uint32_t)(uintptr_t)((lds_ptr)&vs[0][0]);
+  const uint32_t kvs0 = (uint32_t)(uintptr_t)((lds_ptr)&kvs[0][0]);
+  const int p16 = lane & 15, bb = lane >> 4;
+  const int krow0 = 8 * (bb >> 1) + (p16 >> 2);          // staged key row inside a 16-row step
   for (int kb = 0; kb < nkb; ++kb) {
-    if (kb + 1 < nkb) MOE_ATT_LOAD_V(kb + 1)
-    // ---- scores S^T for 64 keys: two 32-key tiles
+    if (kb + 1 < nkb) MOE_ATT_LOAD_KV(kb + 1)
+    const uint32_t kst = kvs0 + (kb & 1) * 2 * kTile, vst = kst + kTile;
+    // ---- scores S^T for 64 keys: two 32-key tiles; lane (r, hf) reads 16 bytes of key row r
     f32x16_t sacc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[t][i] = 0.f;
-      const bf16_t* krow = kbase + (size_t)(kb * 64 + 32 * t + r) * ld + 8 * hf;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(krow + 16 * s);
+        const u32x4_t kf = *(lds_u4_ptr)(uintptr_t)(kst + (32 * t + r) * kPitch + 32 * s + 16 * hf);
         sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
                                                           __builtin_bit_cast(bf16x8_t, qf[s]),
                                                           sacc[t], 0, 0, 0);
@@ -237,33 +245,35 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[t][i] *= sl2; mx = fmaxf(mx, sacc[t][i]); }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[t][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;        // sl2 > 0: scaling commutes with max
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = exp2f(m_run - m_new);            // 0 on the first block (m_run = -inf)
     float psum = 0.f;
     u32x4_t pf[2][2];                                    // P^T fragments: tile t, MFMA step s
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       float p[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { p[i] = exp2f(sacc[t][i] - m_new); psum += p[i]; }
+      for (int i = 0; i < 16; ++i) { p[i] = exp2f(fmaf(sacc[t][i], sl2, -m_new)); psum += p[i]; }
 #pragma unroll
       for (int s = 0; s < 2; ++s)
         pf[t][s] = u32x4_t{pack_bf16x2(p[8 * s], p[8 * s + 1]), pack_bf16x2(p[8 * s + 2], p[8 * s + 3]),
                            pack_bf16x2(p[8 * s + 4], p[8 * s + 5]), pack_bf16x2(p[8 * s + 6], p[8 * s + 7])};
     }
     psum += __shfl_xor(psum, 32, 64);
-    l_run = l_run * alpha + psum;
+    // the running maximum rarely moves after the first blocks: rescale only when some query
+    // of the wavefront needs it (alpha == 1 exactly otherwise)
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+      const float alpha = exp2f(m_run - m_new);          // 0 on the first block (m_run = -inf)
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[t][i] *= alpha;
+    }
+    l_run += psum;
     m_run = m_new;
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[t][i] *= alpha;
     // ---- O^T += V^T . P^T: MFMA step (t, s) covers staged key rows 32 t + 16 s .. + 15
-    const uint32_t vst = vs0 + (kb & 1) * 64 * kVPitch;
-    const int p16 = lane & 15, bb = lane >> 4;
-    const int krow0 = 8 * (bb >> 1) + (p16 >> 2);        // staged key row inside a 16-row step
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -273,20 +283,20 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
           // lane needs V^T[d = 32 dt + lane%32][8 consecutive staged keys of its half]:
           // 16-lane block bb reads rows krow0 (+4), columns 32 dt + 16 (bb&1) + 4 (p16&3) .. +3
           const int col = 32 * dt + 16 * (bb & 1) + 4 * (p16 & 3);
-          const uint32_t pv = vst + (32 * t + 16 * s + krow0) * kVPitch + 2 * col;
+          const uint32_t pv = vst + (32 * t + 16 * s + krow0) * kPitch + 2 * col;
           const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pv);
           const s16x4_t hi =
-              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(pv + 4 * kVPitch));
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(pv + 4 * kPitch));
           const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pf[t][s]),
                                                           o[dt], 0, 0, 0);
         }
     // the other stage was last read one iteration ago, before the previous barrier
-    if (kb + 1 < nkb) MOE_ATT_STORE_V((kb + 1) & 1)
+    if (kb + 1 < nkb) MOE_ATT_STORE_KV((kb + 1) & 1)
     __syncthreads();
   }
-#undef MOE_ATT_LOAD_V
-#undef MOE_ATT_STORE_V
+#undef MOE_ATT_LOAD_KV
+#undef MOE_ATT_STORE_KV
   // o[dt][i]: d = 32 dt + 8 (i/4) + 4 hf + i%4 of query r: four consecutive d per 8-byte store
   const float inv = 1.0f / l_run;
   bf16_t* orow = ctx + ((size_t)b * L + qb * 128 + wave * 32 + r) * A + (size_t)h * D;
