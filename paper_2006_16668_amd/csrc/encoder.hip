@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
     for (int t = 0; t < 2; ++t) {
       float p[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { p[i] = exp2f(fmaf(sacc[t][i], sl2, -m_new)); psum += p[i]; }
+      for (int i = 0; i < 16; ++i) { p[i] = __builtin_amdgcn_exp2f(fmaf(sacc[t][i], sl2, -m_new)); psum += p[i]; }
 #pragma unroll
       for (int s = 0; s < 2; ++s)
         pf[t][s] = u32x4_t{pack_bf16x2(p[8 * s], p[8 * s + 1]), pack_bf16x2(p[8 * s + 2], p[8 * s + 3]),
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
     // the running maximum rarely moves after the first blocks: rescale only when some query
     // of the wavefront needs it (alpha == 1 exactly otherwise)
     if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-      const float alpha = exp2f(m_run - m_new);          // 0 on the first block (m_run = -inf)
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
       l_run *= alpha;
 #pragma unroll
       for (int t = 0; t < DT; ++t)
