@@ -548,7 +548,7 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
 // block waits for that block's HBM latency; split by role, the multiplying wavefronts only wait
 // for L2.  The loader wavefronts keep a ring of RD feature blocks in flight (global -> registers
 // -> LDS stage); both roles pass the same barriers, one per 64-feature block.
-template <int ETW, int PB>
+template <int ETW, int PB, int RB>   // RB: ring of B register sets (power of two), PB < RB steps ahead
 __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
     int S, int M, int E, int nch,
@@ -624,10 +624,10 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
 #undef MOE_GATE_STORE_A
   } else {
     // ---- multiplying wavefronts: B operand of MFMA step ks (= 4 kb + j), column tile t, split
-    // sp: ring of four register sets, slot ks & 3, filled PB steps ahead of its use
+    // sp: ring of RB register sets, slot ks % RB, filled PB steps ahead of its use
     const u32x4_t* bbase = reinterpret_cast<const u32x4_t*>(wgP) + (size_t)wave * ETW * 3 * 64 + lane;
     const int KS = 4 * KB;
-    u32x4_t bq[4][ETW * 3];
+    u32x4_t bq[RB][ETW * 3];
 #define MOE_GATE_LOAD_B(P, ks)                                                           \
   {                                                                                      \
     const int ksc_ = (ks) < KS ? (ks) : KS - 1;                                          \
@@ -637,25 +637,32 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
 #pragma unroll
     for (int p = 0; p < PB; ++p) MOE_GATE_LOAD_B(p, p)
     __syncthreads();
-    for (int kb = 0; kb < KB; ++kb) {
-      const bf16_t* as = As + (kb & 1) * 128 * kAPitch + r * kAPitch + 32 * h;
+    constexpr int KU = RB / 4;                          // feature blocks per trip: slots stay static
+    for (int kb0 = 0; kb0 < KB; kb0 += KU) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        MOE_GATE_LOAD_B((j + PB) & 3, kb * 4 + j + PB)
-        u32x4_t af[4];
+      for (int ku = 0; ku < KU; ++ku) {
+        const int kb = kb0 + ku;
+        if (kb < KB) {                                  // block-uniform
+          const bf16_t* as = As + (kb & 1) * 128 * kAPitch + r * kAPitch + 32 * h;
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt)
-          af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
+          for (int j = 0; j < 4; ++j) {
+            MOE_GATE_LOAD_B((4 * ku + j + PB) % RB, kb * 4 + j + PB)
+            u32x4_t af[4];
 #pragma unroll
-        for (int t = 0; t < ETW; ++t)
+            for (int rt = 0; rt < 4; ++rt)
+              af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
 #pragma unroll
-          for (int rt = 0; rt < 4; ++rt) {
-            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 2], acc[rt][t]);
-            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 1], acc[rt][t]);
-            acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[j][t * 3 + 0], acc[rt][t]);
+            for (int t = 0; t < ETW; ++t)
+#pragma unroll
+              for (int rt = 0; rt < 4; ++rt) {
+                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 2], acc[rt][t]);
+                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 1], acc[rt][t]);
+                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 0], acc[rt][t]);
+              }
           }
+          __syncthreads();
+        }
       }
-      __syncthreads();
     }
 #undef MOE_GATE_LOAD_B
   }
@@ -935,8 +942,8 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
       if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, lds1, st, MOE_GATE_ARGS);
       else hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, lds2, st, MOE_GATE_ARGS);
     }
-    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 3>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
-    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<2, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 6, 8>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<2, 2, 4>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
     else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
 #undef MOE_GATE_ARGS
     rc = check_launch();
