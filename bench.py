@@ -61,6 +61,64 @@ def cpu_baseline(cfg, inp, seconds_hint=20.0):
                       f"fp64 numpy, {t_total:.1f} s; includes widening each expert's weights to fp64"}
 
 
+class PowerSampler:
+    """Board power and shader clock from sysfs while a region runs (a thread polling every few
+    milliseconds); says whether the card sat at its power cap, which is what sets the clock the
+    MFMA-bound kernels run at.  Silent when the files are not there."""
+
+    def __init__(self):
+        import glob
+        dev = sorted(glob.glob("/sys/class/drm/card*/device"))
+        self.dev = dev[0] if dev else None
+        hw = sorted(glob.glob(self.dev + "/hwmon/hwmon*")) if self.dev else []
+        self.hw = hw[0] if hw else None
+        self.samples, self.clocks, self._stop, self._thread = [], [], False, None
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except OSError:
+            return None
+
+    def _poll(self):
+        while not self._stop:
+            p = self._read(self.hw + "/power1_input") if self.hw else None
+            if p:
+                self.samples.append(int(p) / 1e6)
+            c = self._read(self.dev + "/pp_dpm_sclk") if self.dev else None
+            if c:
+                cur = [ln for ln in c.splitlines() if ln.strip().endswith("*")]
+                if cur:
+                    self.clocks.append(int(cur[0].split(":")[1].strip().split("Mhz")[0]))
+            time.sleep(0.002)
+
+    def __enter__(self):
+        import threading
+        self._thread = threading.Thread(target=self._poll, daemon=True)
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return None
+        cap = self._read(self.hw + "/power1_cap")
+        half = self.samples[len(self.samples) // 2:]      # second half: past the ramp of the sensor's average
+        return {"board_power_W_mean": sum(self.samples) / len(self.samples),
+                "board_power_W_second_half": sum(half) / len(half),
+                "board_power_W_max": max(self.samples),
+                "power_cap_W": int(cap) / 1e6 if cap else None,
+                "sclk_MHz_mean": sum(self.clocks) / len(self.clocks) if self.clocks else None,
+                "sclk_MHz_second_half": (sum(self.clocks[len(self.clocks) // 2:]) /
+                                         len(self.clocks[len(self.clocks) // 2:]) if self.clocks else None),
+                "sclk_MHz_nominal": 2400, "samples": len(self.samples)}
+
+
 def yardsticks(cfg, dev):
     """Context for the roofline fractions, measured in the same process on the same box: a
     plain device copy, the vendor library's square bf16 GEMM and its batched GEMMs of exactly
@@ -255,6 +313,12 @@ def main():
         moe.moe_forward_events(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws, events[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # power / clock state under this load: a separate, longer, untimed run of the same calls
+    with PowerSampler() as ps:
+        for _ in range(max(K, int(1500.0 / max((t1 - t0) * 1e3 / K, 0.05)))):      # about 1.5 s
+            moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+        torch.cuda.synchronize()
+    power = ps.summary()
 
     ms_per_step = (t1 - t0) * 1e3 / K
     names = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
@@ -291,6 +355,7 @@ def main():
                      "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
                      "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
+        "power_state": power,
         "stages_ms": stage_ms, "stages_ms_median": stage_median, "stages_ms_min": stage_min,
         # the gate's logits run as three bf16 MFMA passes (wg in three bf16 terms): at E > 64 that,
         # not HBM, bounds the stage
