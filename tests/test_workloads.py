@@ -59,3 +59,24 @@ def test_balanced_workload_drops_few():
     x, wg, u = inp.host_f64()
     r = orc.top2_gating(orc.softmax_gates(x, wg), u, cfg.C)
     assert (r["slot"] == orc.SLOT_OVERFLOW).mean() < 0.03
+
+
+def test_upstream_and_encoder_weight_generators_are_seeded():
+    from workloads import make_encoder_weights, make_upstream
+    cfg = CONFIGS["tiny"]
+    dy1, da1 = make_upstream(cfg)
+    dy2, da2 = make_upstream(cfg)
+    assert dy1.shape == (cfg.G, cfg.S, cfg.M) and da1.shape == (cfg.G,)
+    assert torch.equal(dy1, dy2) and torch.equal(da1, da2)
+    assert not torch.equal(dy1, make_upstream(cfg.with_(seed=cfg.seed + 1))[0])
+    small = CONFIGS["small"]
+    assert make_upstream(small)[0].dtype == torch.bfloat16
+    w1 = make_encoder_weights(small, heads=4, d=16)
+    w2 = make_encoder_weights(small, heads=4, d=16)
+    assert w1["wqkv"][0].shape == (small.M, 3 * 64) and w1["wo_att"][1].shape == (64, small.M)
+    assert w1["w1"].shape == (small.M, small.H) and w1["w1"].dtype == torch.bfloat16
+    assert w1["ln_gamma"][3].dtype == torch.float32
+    for k in ("wqkv", "wo_att", "ln_gamma", "ln_beta"):
+        for a, b in zip(w1[k], w2[k]):
+            assert torch.equal(a, b)
+    assert not torch.equal(w1["wqkv"][0], w1["wqkv"][1])          # the two attention layers differ
