@@ -163,9 +163,13 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
     const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, int L, int heads) {
   constexpr int KS = D / 16;                 // MFMA steps over d for the scores
   constexpr int DT = D / 32;                 // 32-row tiles of O^T
-  constexpr int kPitch = D * 2 + 16;         // bytes per staged K / V row (16-byte pad: bank spread)
-  constexpr int kTile = 64 * kPitch;         // one staged block of 64 keys
-  __shared__ __attribute__((aligned(16))) unsigned char kvs[2][2 * kTile];   // stage: K block, V block
+  // Row pitches of the staged blocks, chosen for the 64 LDS banks: the 16-byte K reads of 16
+  // consecutive rows must start 4 banks apart (pitch = 4 words mod 64), the transposing 8-byte V
+  // reads of a half-wavefront touch 4 rows x 16 words (pitch = 16 words mod 64).
+  constexpr int kKPitch = D * 2 + 16, kVPitch = D * 2 + 64;
+  constexpr int kKTile = 64 * kKPitch;       // one staged K block of 64 keys (the V block follows it)
+  constexpr int kStage = kKTile + 64 * kVPitch;
+  __shared__ __attribute__((aligned(16))) unsigned char kvs[2][kStage];      // stage: K block, V block
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hf = lane >> 5;
   const int qblocks = L / 128;
@@ -209,8 +213,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
   _Pragma("unroll") for (int i = 0; i < VV; ++i) {                                            \
     const int f = tid + 256 * i, key = f / VPR, c = f % VPR;                                  \
     const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1); /* swap bits 2, 3 */   \
-    *reinterpret_cast<u32x4_t*>(&kvs[stage][key * kPitch + 16 * c]) = kreg[i];                \
-    *reinterpret_cast<u32x4_t*>(&kvs[stage][kTile + pos * kPitch + 16 * c]) = vreg[i];        \
+    *reinterpret_cast<u32x4_t*>(&kvs[stage][key * kKPitch + 16 * c]) = kreg[i];               \
+    *reinterpret_cast<u32x4_t*>(&kvs[stage][kKTile + pos * kVPitch + 16 * c]) = vreg[i];      \
   }
   const int nkb = L / 64;
   MOE_ATT_LOAD_KV(0)
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
   const int krow0 = 8 * (bb >> 1) + (p16 >> 2);          // staged key row inside a 16-row step
   for (int kb = 0; kb < nkb; ++kb) {
     if (kb + 1 < nkb) MOE_ATT_LOAD_KV(kb + 1)
-    const uint32_t kst = kvs0 + (kb & 1) * 2 * kTile, vst = kst + kTile;
+    const uint32_t kst = kvs0 + (kb & 1) * kStage, vst = kst + kKTile;
     // ---- scores S^T for 64 keys: two 32-key tiles; lane (r, hf) reads 16 bytes of key row r
     f32x16_t sacc[2];
 #pragma unroll
@@ -234,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
       for (int i = 0; i < 16; ++i) sacc[t][i] = 0.f;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const u32x4_t kf = *(lds_u4_ptr)(uintptr_t)(kst + (32 * t + r) * kPitch + 32 * s + 16 * hf);
+        const u32x4_t kf = *(lds_u4_ptr)(uintptr_t)(kst + (32 * t + r) * kKPitch + 32 * s + 16 * hf);
         sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
                                                           __builtin_bit_cast(bf16x8_t, qf[s]),
                                                           sacc[t], 0, 0, 0);
@@ -283,10 +287,10 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
           // lane needs V^T[d = 32 dt + lane%32][8 consecutive staged keys of its half]:
           // 16-lane block bb reads rows krow0 (+4), columns 32 dt + 16 (bb&1) + 4 (p16&3) .. +3
           const int col = 32 * dt + 16 * (bb & 1) + 4 * (p16 & 3);
-          const uint32_t pv = vst + (32 * t + 16 * s + krow0) * kPitch + 2 * col;
+          const uint32_t pv = vst + (32 * t + 16 * s + krow0) * kVPitch + 2 * col;
           const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)pv);
           const s16x4_t hi =
-              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(pv + 4 * kPitch));
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(pv + 4 * kVPitch));
           const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8_t, pf[t][s]),
                                                           o[dt], 0, 0, 0);
