@@ -834,11 +834,14 @@ int launch_topk(const moe_config& c, int nch, const T* x, const float* wg, const
 // past 3E zero: the K-contiguous B operand of a plain GEMM x . wgk^T whose fp32 result holds the
 // three partial logits of every expert side by side.
 namespace {
+// K = reps * M: the row is repeated `reps` times along K (fp32 activations enter the product as
+// three bf16 terms side by side, each of which meets every term of wg).
 __global__ __launch_bounds__(256) void gate_pack_wide_kernel(
-    const float* __restrict__ wg, bf16_t* __restrict__ wgk, int M, int E, int cols) {
+    const float* __restrict__ wg, bf16_t* __restrict__ wgk, int M, int E, int cols, int reps) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (long long)cols * M) return;
-  const int c = (int)(i / M), m = (int)(i % M);
+  const int K = reps * M;
+  if (i >= (long long)cols * K) return;
+  const int c = (int)(i / K), m = (int)(i % K) % M;
   bf16_t out = 0;
   if (c < 3 * E) {
     const float v = wg[(size_t)m * E + c / 3];
@@ -850,21 +853,42 @@ __global__ __launch_bounds__(256) void gate_pack_wide_kernel(
   }
   wgk[i] = out;
 }
+
+// xk[n, a*M + m] = term a (hi, mid, lo) of the fp32 activation x[n,m]: x = hi + mid + lo exactly
+__global__ __launch_bounds__(256) void gate_split_x_kernel(
+    const float* __restrict__ x, bf16_t* __restrict__ xk, int M, long long tokens) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= tokens * M) return;
+  const long long n = i / M;
+  const int m = (int)(i % M);
+  const float v = x[i];
+  const bf16_t hi = f32_to_bf16(v);
+  const float r1 = v - bf16_to_f32(hi);
+  const bf16_t mid = f32_to_bf16(r1);
+  bf16_t* d = xk + n * 3 * M + m;
+  d[0] = hi;
+  d[M] = mid;
+  d[2 * (size_t)M] = f32_to_bf16(r1 - bf16_to_f32(mid));
+}
 }  // namespace
 
-// E > 512 on the matrix cores: needs the persistent GEMM's shapes (token count a multiple of
-// 256, M of 32) and at most 2048 experts (registers of the epilogue kernel).
-struct WideGeom { int cols; size_t z_bytes, w_bytes; };
+// Logits as one GEMM on the matrix cores, for bf16 gates wider than 512 experts and for fp32
+// activations (x split into three bf16 terms, K = 3 M): needs the persistent GEMM's shapes (token
+// count a multiple of 256, K of 32) and at most 2048 experts (registers of the epilogue kernel).
+struct WideGeom { int cols, k; size_t z_bytes, w_bytes, x_bytes; };
 static WideGeom wide_geom(const moe_config& c) {
   WideGeom w{};
   const long long tokens = (long long)c.G * c.S;
   const long long cols = ((long long)3 * c.E + 255) / 256 * 256;
-  if (c.act_dtype != MOE_BF16 || c.E <= 512 || c.E > 2048 || tokens > 0x7fffffffLL ||
-      !gemm_bf16_f32out_ok((int)tokens, (int)cols, c.M))
+  const long long k = c.act_dtype == MOE_F32 ? (long long)3 * c.M : c.M;
+  if ((c.act_dtype == MOE_BF16 && c.E <= 512) || c.E > 2048 || tokens > 0x7fffffffLL ||
+      k > 0x7fffffffLL || !gemm_bf16_f32out_ok((int)tokens, (int)cols, (int)k))
     return w;
   w.cols = (int)cols;
+  w.k = (int)k;
   w.z_bytes = (size_t)tokens * cols * 4;
-  w.w_bytes = (size_t)cols * c.M * 2;
+  w.w_bytes = (size_t)cols * k * 2;
+  w.x_bytes = c.act_dtype == MOE_F32 ? (size_t)tokens * k * 2 : 0;
   return w;
 }
 
@@ -884,7 +908,7 @@ size_t gate_workspace_bytes(const moe_config& c) {
   const size_t nch = (size_t)(c.S + kChunk - 1) / kChunk;
   const WideGeom w = wide_geom(c);
   return 3 * align_up((size_t)c.G * nch * c.E * 4, 256) + align_up(pack_geom(c).bytes, 256) +
-         align_up(w.w_bytes, 256) + align_up(w.z_bytes, 256);
+         align_up(w.w_bytes, 256) + align_up(w.z_bytes, 256) + align_up(w.x_bytes, 256);
 }
 
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
@@ -899,22 +923,36 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
   uint4* wgP = reinterpret_cast<uint4*>(static_cast<char*>(ws) + 3 * seg);
   const PackGeom pg = pack_geom(c);
   int rc;
-  if (c.act_dtype == MOE_F32) {
+  if (wide_geom(c).cols != 0) {
+    // pg.bytes == 0 here: the packed-operand region is empty; wgk, the logits and (fp32) the
+    // split activations follow it
+    const WideGeom w = wide_geom(c);
+    const long long tokens = (long long)c.G * c.S;
+    bf16_t* wgk = reinterpret_cast<bf16_t*>(wgP);
+    char* after = reinterpret_cast<char*>(wgP) + align_up(w.w_bytes, 256);
+    float* zpre = reinterpret_cast<float*>(after);
+    bf16_t* xk = reinterpret_cast<bf16_t*>(after + align_up(w.z_bytes, 256));
+    const long long n = (long long)w.cols * w.k;
+    hipLaunchKernelGGL(gate_pack_wide_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
+                       wgk, c.M, c.E, w.cols, w.k / c.M);
+    if ((rc = check_launch()) != MOE_OK) return rc;
+    const void* a = x;
+    if (c.act_dtype == MOE_F32) {
+      hipLaunchKernelGGL(gate_split_x_kernel, dim3((unsigned)((tokens * c.M + 255) / 256)), dim3(256),
+                         0, st, static_cast<const float*>(x), xk, c.M, tokens);
+      if ((rc = check_launch()) != MOE_OK) return rc;
+      a = xk;
+    }
+    rc = launch_gemm_bf16_f32out(false, a, wgk, zpre, 1, (int)tokens, w.cols, w.k, st);
+    if (rc != MOE_OK) return rc;
+    rc = c.act_dtype == MOE_F32
+             ? launch_topk<float, true>(c, nch, static_cast<const float*>(x), wg, u, expert_idx, slot,
+                                        weight, gates_opt, hist1, hist2, msum, st, zpre, w.cols)
+             : launch_topk<bf16_t, true>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx,
+                                         slot, weight, gates_opt, hist1, hist2, msum, st, zpre, w.cols);
+  } else if (c.act_dtype == MOE_F32) {
     rc = launch_topk<float>(c, nch, static_cast<const float*>(x), wg, u, expert_idx, slot, weight,
                             gates_opt, hist1, hist2, msum, st);
-  } else if (wide_geom(c).cols != 0) {
-    // pg.bytes == 0 here: the packed-operand region is empty, wgk and the logits follow it
-    const WideGeom w = wide_geom(c);
-    bf16_t* wgk = reinterpret_cast<bf16_t*>(wgP);
-    float* zpre = reinterpret_cast<float*>(reinterpret_cast<char*>(wgP) + align_up(w.w_bytes, 256));
-    const long long n = (long long)w.cols * c.M;
-    hipLaunchKernelGGL(gate_pack_wide_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
-                       wgk, c.M, c.E, w.cols);
-    if ((rc = check_launch()) != MOE_OK) return rc;
-    rc = launch_gemm_bf16_f32out(false, x, wgk, zpre, 1, c.G * c.S, w.cols, c.M, st);
-    if (rc != MOE_OK) return rc;
-    rc = launch_topk<bf16_t, true>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
-                                   weight, gates_opt, hist1, hist2, msum, st, zpre, w.cols);
   } else if (pg.bytes == 0) {
     rc = launch_topk<bf16_t>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
                              weight, gates_opt, hist1, hist2, msum, st);

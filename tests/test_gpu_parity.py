@@ -55,6 +55,9 @@ SMALL_CASES = [
     # cores with wg in three bf16 terms, then a per-token softmax / top-2 pass
     MoEConfig("e640_wide", G=2, S=512, M=256, H=32, E=640, C=2, act_dtype="bf16", seed=34),
     MoEConfig("e2048_wide", G=1, S=1024, M=128, H=32, E=2048, C=1, act_dtype="bf16", seed=35),
+    # fp32 activations with GEMM-friendly shapes: logits on the matrix cores with x and wg each in
+    # three bf16 terms (all nine exact products)
+    MoEConfig("f32_mfma_gate", G=2, S=256, M=64, H=64, E=12, C=64, act_dtype="f32", seed=36),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
 ]
 
