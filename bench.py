@@ -242,6 +242,58 @@ def time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak):
             "note": "moe_backward after moe_forward_train on the same inputs; not part of value"}
 
 
+def time_f32_layer(moe, cfg, K, W):
+    """The same workload with fp32 activations and expert weights (the precision the paper
+    trained in, Section 4): forward and backward of the layer, whose expert GEMMs run as fp32
+    MFMA.  Not part of `value`."""
+    import dataclasses
+    import torch
+    from workloads import make_inputs, make_upstream
+    dev = "cuda:0"
+    c32 = dataclasses.replace(cfg, name=cfg.name + "_f32", act_dtype="f32")
+    inp = make_inputs(c32, device=dev)
+    sh = moe.MoEShape(c32.G, c32.S, c32.M, c32.H, c32.E, c32.C, "f32")
+    y = torch.empty_like(inp.x)
+    aux = torch.empty(c32.G, dtype=torch.float32, device=dev)
+    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
+    for e in evs:
+        e.record()
+    for _ in range(W):
+        moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+    torch.cuda.synchronize()
+    names = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
+    stage = {n: 0.0 for n in names}
+    t0 = time.perf_counter()
+    for _ in range(K):
+        moe.moe_forward_events(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws, evs)
+    torch.cuda.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / K
+    for i, n in enumerate(names):                  # stage times of the last call
+        stage[n] = evs[i].elapsed_time(evs[i + 1])
+    padded = c32.E * c32.G * c32.C
+    gemm_ms = stage["expert_gemm1"] + stage["expert_gemm2"]
+    dy, daux = make_upstream(c32, device=dev)
+    dx, dwg = torch.empty_like(inp.x), torch.empty_like(inp.wg)
+    dwi, dwo = torch.empty_like(inp.wi), torch.empty_like(inp.wo)
+    bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_forward_train(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+    args = (sh, inp.x, inp.wg, inp.wi, inp.wo, dy, daux, ws, dx, dwg, dwi, dwo, bws)
+    moe.moe_backward(*args)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        moe.moe_backward(*args)
+    torch.cuda.synchronize()
+    bwd_ms = (time.perf_counter() - t0) * 1e3 / K
+    return {"forward_ms_per_step": fwd_ms, "forward_tokens_per_s": c32.N / (fwd_ms * 1e-3),
+            "stages_ms": stage, "backward_ms_per_step": bwd_ms,
+            # every slot is multiplied (no skipping of empty rows), so padded rows are the work
+            "ffn_mfma_f32_frac_padded_rows": 4.0 * c32.M * c32.H * padded / (gemm_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS,
+            "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
+            "note": "same workload in fp32 (v_mfma_f32_32x32x2_f32); not part of value"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -256,6 +308,8 @@ def main():
                     help="skip the extra measurement of the encoder layers around the MoE layer")
     ap.add_argument("--no-yardsticks", action="store_true",
                     help="skip the copy / vendor-GEMM context measurements")
+    ap.add_argument("--no-f32", action="store_true",
+                    help="skip the extra measurement of the same workload in fp32")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the extra (untimed for the metric) measurement of the backward pass")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -350,7 +404,8 @@ def main():
         "config": {"workload": f"{cfg.name}: G={cfg.G} S={cfg.S} M={cfg.M} H={cfg.H} E={cfg.E} "
                                f"C={cfg.C}, top-2, {cfg.act_dtype} experts, fp32 gate",
                    "tokens": cfg.N, "kept_rows": kept_rows, "padded_rows": padded_rows},
-        "roofline": {"bound": "mfma", "kernel": f"expert_gemm_bf16_dma_kernel ({dom})",
+        "roofline": {"bound": "mfma", "kernel": ("expert_gemm_bf16_dma_kernel" if cfg.act_dtype == "bf16"
+                                                   else "gemm_f32_mfma_kernel") + f" ({dom})",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
@@ -384,6 +439,10 @@ def main():
         out["yardsticks"] = yardsticks(cfg, dev)
     if not args.no_backward:
         out["backward"] = time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak)
+    if not args.no_f32 and cfg.act_dtype == "bf16":
+        del ws, y
+        torch.cuda.empty_cache()
+        out["f32_layer"] = time_f32_layer(moe, cfg, min(K, 5), min(W, 2))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(out))

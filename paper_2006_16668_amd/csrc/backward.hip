@@ -348,6 +348,12 @@ int gemm_strided(int epi, const void* A, long long a_e, long long a_r, long long
 int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a_e, long long a_r,
                         long long a_k, const void* B, long long b_e, long long b_k, long long b_n,
                         void* Cout, const void* mask, int R, int N, int K, hipStream_t st) {
+  if (c.act_dtype == MOE_F32 && R > 0 && N > 0 && K > 0 && a_e % 4 == 0 && b_e % 4 == 0 &&
+      gemm_f32_mfma_ok(a_r, a_k, b_k, b_n, c.E, R, N, K))
+    return launch_gemm_f32_mfma(epi, static_cast<const float*>(A), a_e, a_r, a_k,
+                                static_cast<const float*>(B), b_e, b_k, b_n,
+                                static_cast<float*>(Cout), static_cast<const float*>(mask), c.E, R,
+                                N, K, st);
   return c.act_dtype == MOE_F32
              ? gemm_strided<float>(epi, A, a_e, a_r, a_k, B, b_e, b_k, b_n, Cout, mask, c.E, R, N, K, st)
              : gemm_strided<bf16_t>(epi, A, a_e, a_r, a_k, B, b_e, b_k, b_n, Cout, mask, c.E, R, N, K, st);

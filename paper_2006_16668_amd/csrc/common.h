@@ -165,6 +165,14 @@ bool gemm_bf16_f32out_ok(int R, int N, int K);
 int launch_gemm_bf16_f32out(bool transposed_a, const void* A, const void* B, float* Cout,
                             int batch, int R, int N, int K, hipStream_t st);
 
+// fp32 GEMM on the matrix cores (gemm_f32.hip), strides as in launch_gemm_strided; every operand
+// needs one unit stride and 16-byte alignment along it (gemm_f32_mfma_ok says whether it fits)
+bool gemm_f32_mfma_ok(long long a_r, long long a_k, long long b_k, long long b_n, int E, int R, int N,
+                      int K);
+int launch_gemm_f32_mfma(int epi, const float* A, long long a_e, long long a_r, long long a_k,
+                         const float* B, long long b_e, long long b_k, long long b_n, float* Cout,
+                         const float* mask, int E, int R, int N, int K, hipStream_t st);
+
 // Transformer encoder sub-layers around the MoE layer (encoder.hip)
 int launch_add_layer_norm(int act_dtype, const void* x, const void* delta, const float* gamma,
                           const float* beta, void* sum_out, void* norm_out, long long rows, int M,

@@ -712,59 +712,15 @@ int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int 
 }
 
 // ---------------------------------------------------------------- fp32 path
-template <bool RELU>
-__global__ __launch_bounds__(256) void expert_gemm_f32_kernel(
-    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ Cout,
-    int R, int N, int K, int tiles_m, int tiles_n) {
-  constexpr int T = 64, BK = 16;
-  __shared__ float As[BK][T + 1];
-  __shared__ float Bs[BK][T + 1];
-  const int per_e = tiles_m * tiles_n;
-  const int e = blockIdx.x / per_e, t = blockIdx.x % per_e;
-  const int m0 = (t % tiles_m) * T, n0 = (t / tiles_m) * T;
-  const float* Ae = A + (size_t)e * R * K;
-  const float* Be = B + (size_t)e * K * N;
-  float* Ce = Cout + (size_t)e * R * N;
-  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  float acc[4][4] = {};
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    for (int i = threadIdx.x; i < T * BK; i += 256) {
-      const int r = i / BK, k = i % BK;
-      As[k][r] = (m0 + r < R && k0 + k < K) ? Ae[(size_t)(m0 + r) * K + k0 + k] : 0.f;
-      const int kb = i / T, c = i % T;
-      Bs[kb][c] = (k0 + kb < K && n0 + c < N) ? Be[(size_t)(k0 + kb) * N + n0 + c] : 0.f;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < BK; ++k) {
-      float a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-    }
-    __syncthreads();
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = m0 + ty * 4 + i, c = n0 + tx * 4 + j;
-      if (r < R && c < N) Ce[(size_t)r * N + c] = RELU ? fmaxf(acc[i][j], 0.f) : acc[i][j];
-    }
-}
-
+// fp32 layers multiply on the matrix cores in full fp32 (gemm_f32.hip); M and H are multiples
+// of 8, so every operand meets that kernel's 16-byte rule.
 template <bool RELU>
 int gemm_f32(const float* A, const float* B, float* Cout, int E, int R, int N, int K,
              hipStream_t st) {
-  const int tiles_m = (R + 63) / 64, tiles_n = (N + 63) / 64;
-  const long long nblk = (long long)E * tiles_m * tiles_n;
-  if (nblk > 0x7fffffffLL) return MOE_EUNSUPPORTED;
-  hipLaunchKernelGGL(expert_gemm_f32_kernel<RELU>, dim3((unsigned)nblk), dim3(256), 0, st, A, B,
-                     Cout, R, N, K, tiles_m, tiles_n);
-  return check_launch();
+  const long long ae = (long long)R * K, be = (long long)K * N;
+  if (ae % 4 != 0 || be % 4 != 0 || !gemm_f32_mfma_ok(K, 1, N, 1, E, R, N, K))
+    return MOE_EUNSUPPORTED;
+  return launch_gemm_f32_mfma(RELU ? 1 : 0, A, ae, K, 1, B, be, N, 1, Cout, nullptr, E, R, N, K, st);
 }
 
 }  // namespace

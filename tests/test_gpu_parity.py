@@ -58,6 +58,9 @@ SMALL_CASES = [
     # fp32 activations with GEMM-friendly shapes: logits on the matrix cores with x and wg each in
     # three bf16 terms (all nine exact products)
     MoEConfig("f32_mfma_gate", G=2, S=256, M=64, H=64, E=12, C=64, act_dtype="f32", seed=36),
+    # fp32 expert GEMMs on the matrix cores: several 128 x 128 tiles with ragged tails in rows,
+    # columns and K (rows per expert = 303, no multiple of 4 either)
+    MoEConfig("f32_tiles", G=3, S=200, M=136, H=264, E=3, C=101, act_dtype="f32", seed=37),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
 ]
 
