@@ -293,6 +293,44 @@ int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims
                              const moe_encoder_weights* w, const float* u, void* y, float* aux,
                              void* ws, size_t ws_bytes, void* stream);
 
+/* ---- training of the two encoder layers ----------------------------------------------------
+ * The paper trains the model by automatic differentiation (Section 2.1 names the sub-layers,
+ * Section 3.1 the MoE layer); these entry points evaluate the derivative of
+ *     L = sum dy * y + sum_g daux[g] * aux[g]
+ * for the pair of layers above by the chain rule: layer normalisation, the attention
+ * projections and the scaled dot-product core (probabilities recomputed from q, k and a stored
+ * row statistic), the dense feed-forward layer (relu'(0) = 0) and the MoE layer
+ * (moe_backward).  Residual branches add their gradients. */
+typedef struct {       /* device pointers to the outputs, owned by the caller; shapes as the weights */
+  float *ln_gamma[4], *ln_beta[4];
+  void *wqkv[2];
+  void *wo_att[2];
+  void *w1, *w2;
+  float *wg;
+  void *wi, *wo;
+} moe_encoder_grads;
+
+/* Bytes of workspace of moe_encoder_pair_forward_train / moe_encoder_pair_backward.  Host only. */
+int moe_encoder_train_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes);
+int moe_encoder_backward_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes);
+
+/* moe_encoder_pair_forward with the same result, keeping in ws (>= moe_encoder_train_workspace_bytes,
+ * 256-byte aligned) what the backward pass reads: the four normalised inputs, the residual sums,
+ * q|k|v, the attention context and its row statistic per layer, the hidden activations of the
+ * dense layer and the MoE layer's training workspace.  ws must stay untouched until
+ * moe_encoder_pair_backward has run. */
+int moe_encoder_pair_forward_train(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                                   const moe_encoder_weights* w, const float* u, void* y, float* aux,
+                                   void* ws, size_t ws_bytes, void* stream);
+
+/* in: x, w as in the forward call; dy [B,L,M] (activation dtype), daux [G] fp32; fwd_ws as left by
+ * moe_encoder_pair_forward_train.  out: dx [B,L,M]; every member of g (fully overwritten).
+ * ws >= moe_encoder_backward_workspace_bytes, 256-byte aligned.  Errors as the other calls. */
+int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                              const moe_encoder_weights* w, const void* dy, const float* daux,
+                              const void* fwd_ws, size_t fwd_ws_bytes, void* dx,
+                              const moe_encoder_grads* g, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,6 +7,8 @@ There is no CPU fallback: a missing library raises on first use.
 """
 from .binding import (EncoderDims, moe_add_layer_norm, moe_attention_workspace_bytes,
                       moe_dense_ffn, moe_encoder_pair_forward, moe_encoder_workspace_bytes,
+                      moe_encoder_pair_forward_train, moe_encoder_pair_backward,
+                      moe_encoder_train_workspace_bytes, moe_encoder_backward_workspace_bytes,
                       moe_self_attention, moe_backward, moe_backward_events, moe_backward_workspace_bytes,
                       moe_forward_train, MoEError, MoEShape, library_path, load_library, moe_combine, moe_dispatch,
                       moe_expert_ffn, moe_forward, moe_forward_events, moe_forward_fuses_dispatch,
@@ -15,6 +17,8 @@ from .binding import (EncoderDims, moe_add_layer_norm, moe_attention_workspace_b
 
 __all__ = ["EncoderDims", "moe_add_layer_norm", "moe_attention_workspace_bytes", "moe_dense_ffn",
            "moe_encoder_pair_forward", "moe_encoder_workspace_bytes", "moe_self_attention",
+           "moe_encoder_pair_forward_train", "moe_encoder_pair_backward",
+           "moe_encoder_train_workspace_bytes", "moe_encoder_backward_workspace_bytes",
            "moe_backward", "moe_backward_events", "moe_backward_workspace_bytes",
            "moe_forward_train", "MoEError", "MoEShape", "library_path", "load_library", "moe_combine", "moe_dispatch",
            "moe_expert_ffn", "moe_forward", "moe_forward_events", "moe_forward_fuses_dispatch",

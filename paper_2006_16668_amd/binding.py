@@ -25,7 +25,9 @@ EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes
            "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
            "moe_backward", "moe_backward_events", "moe_add_layer_norm",
            "moe_attention_workspace_bytes", "moe_encoder_workspace_bytes", "moe_self_attention",
-           "moe_dense_ffn", "moe_encoder_pair_forward")
+           "moe_dense_ffn", "moe_encoder_pair_forward", "moe_encoder_train_workspace_bytes",
+           "moe_encoder_backward_workspace_bytes", "moe_encoder_pair_forward_train",
+           "moe_encoder_pair_backward")
 FORWARD_EVENTS = 6
 BACKWARD_EVENTS = 8
 
@@ -120,6 +122,13 @@ def load_library() -> ctypes.CDLL:
         "moe_dense_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
         "moe_encoder_pair_forward": [cfgp, ctypes.POINTER(_EncoderDims), vp,
                                      ctypes.POINTER(_EncoderWeights), vp, vp, vp, vp, sz, vp],
+        "moe_encoder_train_workspace_bytes": [cfgp, ctypes.POINTER(_EncoderDims), ctypes.POINTER(sz)],
+        "moe_encoder_backward_workspace_bytes": [cfgp, ctypes.POINTER(_EncoderDims), ctypes.POINTER(sz)],
+        "moe_encoder_pair_forward_train": [cfgp, ctypes.POINTER(_EncoderDims), vp,
+                                           ctypes.POINTER(_EncoderWeights), vp, vp, vp, vp, sz, vp],
+        "moe_encoder_pair_backward": [cfgp, ctypes.POINTER(_EncoderDims), vp,
+                                      ctypes.POINTER(_EncoderWeights), vp, vp, vp, sz, vp,
+                                      ctypes.POINTER(_EncoderWeights), vp, sz, vp],
         "moe_backward_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_backward": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp],
         "moe_backward_events": [cfgp] + [vp] * 7 + [sz] + [vp] * 5 + [sz, vp,
@@ -365,10 +374,9 @@ def moe_dense_ffn(shape: MoEShape, u, w1, w2, h_ws, out):
         _ptr(h_ws, dt, (G, S, H), "h_ws"), _ptr(out, dt, (G, S, M), "out"), _stream()), "moe_dense_ffn")
 
 
-def moe_encoder_pair_forward(shape: MoEShape, dims: EncoderDims, x, weights: dict, u, y, aux, ws):
-    """weights: ln_gamma / ln_beta (4 tensors [M] fp32 each), wqkv / wo_att (2 each), w1, w2,
-    wg, wi, wo."""
-    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+def _encoder_weights(shape: MoEShape, dims: EncoderDims, weights: dict) -> _EncoderWeights:
+    """The C struct of device pointers (weights, or gradients of the same shapes)."""
+    M, H, E = shape.M, shape.H, shape.E
     A = dims.heads * dims.d
     dt, f32 = shape.torch_dtype, torch.float32
     w = _EncoderWeights()
@@ -383,9 +391,53 @@ def moe_encoder_pair_forward(shape: MoEShape, dims: EncoderDims, x, weights: dic
     w.wg = _ptr(weights["wg"], f32, (M, E), "wg").value
     w.wi = _ptr(weights["wi"], dt, (E, M, H), "wi").value
     w.wo = _ptr(weights["wo"], dt, (E, H, M), "wo").value
+    return w
+
+
+def _encoder_forward(fn_name, shape, dims, x, weights, u, y, aux, ws):
+    G, S, M = shape.G, shape.S, shape.M
+    dt, f32 = shape.torch_dtype, torch.float32
+    w = _encoder_weights(shape, dims, weights)
     c, d = shape._c(), dims._c()
     wsp, wsn = _ws(ws)
-    _check(load_library().moe_encoder_pair_forward(
+    _check(getattr(load_library(), fn_name)(
         ctypes.byref(c), ctypes.byref(d), _ptr(x, dt, (G, S, M), "x"), ctypes.byref(w),
         _ptr(u, f32, (G, S), "u"), _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"),
-        wsp, wsn, _stream()), "moe_encoder_pair_forward")
+        wsp, wsn, _stream()), fn_name)
+
+
+def moe_encoder_pair_forward(shape: MoEShape, dims: EncoderDims, x, weights: dict, u, y, aux, ws):
+    """weights: ln_gamma / ln_beta (4 tensors [M] fp32 each), wqkv / wo_att (2 each), w1, w2,
+    wg, wi, wo."""
+    _encoder_forward("moe_encoder_pair_forward", shape, dims, x, weights, u, y, aux, ws)
+
+
+def moe_encoder_train_workspace_bytes(shape: MoEShape, dims: EncoderDims) -> int:
+    return _ws_query("moe_encoder_train_workspace_bytes", shape, dims)
+
+
+def moe_encoder_backward_workspace_bytes(shape: MoEShape, dims: EncoderDims) -> int:
+    return _ws_query("moe_encoder_backward_workspace_bytes", shape, dims)
+
+
+def moe_encoder_pair_forward_train(shape: MoEShape, dims: EncoderDims, x, weights: dict, u, y, aux, ws):
+    """As moe_encoder_pair_forward; ws (moe_encoder_train_workspace_bytes) keeps what
+    moe_encoder_pair_backward reads."""
+    _encoder_forward("moe_encoder_pair_forward_train", shape, dims, x, weights, u, y, aux, ws)
+
+
+def moe_encoder_pair_backward(shape: MoEShape, dims: EncoderDims, x, weights: dict, dy, daux, fwd_ws,
+                              dx, grads: dict, ws):
+    """grads: a dict of output tensors with the keys and shapes of ``weights``."""
+    G, S, M = shape.G, shape.S, shape.M
+    dt, f32 = shape.torch_dtype, torch.float32
+    w = _encoder_weights(shape, dims, weights)
+    g = _encoder_weights(shape, dims, grads)
+    c, d = shape._c(), dims._c()
+    fwp, fwn = _ws(fwd_ws)
+    wsp, wsn = _ws(ws)
+    _check(load_library().moe_encoder_pair_backward(
+        ctypes.byref(c), ctypes.byref(d), _ptr(x, dt, (G, S, M), "x"), ctypes.byref(w),
+        _ptr(dy, dt, (G, S, M), "dy"), _ptr(daux, f32, (G,), "daux"), fwp, fwn,
+        _ptr(dx, dt, (G, S, M), "dx"), ctypes.byref(g), wsp, wsn, _stream()),
+        "moe_encoder_pair_backward")

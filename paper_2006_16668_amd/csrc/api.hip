@@ -187,15 +187,90 @@ EncoderWs carve_enc(const moe_config& c, const moe_encoder_dims& d) {
 }
 
 int attention_impl(const moe_config& c, const moe_encoder_dims& d, const void* u, const void* wqkv,
-                   const void* wo_att, void* out, char* ws, hipStream_t st) {
-  const AttentionWs w = carve_att(c, d);
+                   const void* wo_att, void* out, void* qkv, void* ctx, float* lse, hipStream_t st) {
   const long long N = (long long)c.G * c.S;
   const int A = d.heads * d.d;
-  int rc = dense_gemm(c, N, c.M, 3 * A, false, u, wqkv, ws + w.qkv, st);
+  int rc = dense_gemm(c, N, c.M, 3 * A, false, u, wqkv, qkv, st);
   if (rc != MOE_OK) return rc;
-  rc = moe::launch_attention_core(c.act_dtype, ws + w.qkv, ws + w.ctx, d.B, d.L, d.heads, d.d, st);
+  rc = moe::launch_attention_core(c.act_dtype, qkv, ctx, lse, d.B, d.L, d.heads, d.d, st);
   if (rc != MOE_OK) return rc;
-  return dense_gemm(c, N, A, c.M, false, ws + w.ctx, wo_att, out, st);
+  return dense_gemm(c, N, A, c.M, false, ctx, wo_att, out, st);
+}
+
+// Training form of the pair: every sub-layer keeps what its derivative needs.
+struct EncoderTrainWs { size_t n[4], a, b, c, sub, hden, qkv[2], ctx[2], lse[2], moe, total; };
+EncoderTrainWs carve_enc_train(const moe_config& c, const moe_encoder_dims& d) {
+  const size_t N = (size_t)c.G * c.S, A = (size_t)d.heads * d.d;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  EncoderTrainWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  for (int i = 0; i < 4; ++i) w.n[i] = take(N * c.M * elt);
+  w.a = take(N * c.M * elt);
+  w.b = take(N * c.M * elt);
+  w.c = take(N * c.M * elt);
+  w.sub = take(N * c.M * elt);
+  w.hden = take(N * c.H * elt);
+  for (int i = 0; i < 2; ++i) {
+    w.qkv[i] = take(N * 3 * A * elt);
+    w.ctx[i] = take(N * A * elt);
+    w.lse[i] = take((size_t)d.B * d.heads * d.L * sizeof(float));
+  }
+  w.moe = take(carve(c).total);
+  w.total = off;
+  return w;
+}
+
+struct EncoderBwdWs { size_t g[2], dn, dqkv, dctx, dhden, dvec, partial, moe, total; };
+EncoderBwdWs carve_enc_bwd(const moe_config& c, const moe_encoder_dims& d) {
+  const size_t N = (size_t)c.G * c.S, A = (size_t)d.heads * d.d;
+  const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
+  EncoderBwdWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.g[0] = take(N * c.M * elt);
+  w.g[1] = take(N * c.M * elt);
+  w.dn = take(N * c.M * elt);
+  w.dqkv = take(N * 3 * A * elt);
+  w.dctx = take(N * A * elt);
+  w.dhden = take(N * c.H * elt);
+  w.dvec = take((size_t)d.B * d.heads * d.L * sizeof(float));
+  w.partial = take((size_t)moe::layer_norm_bwd_parts((long long)N) * 2 * c.M * sizeof(float));
+  w.moe = take(carve_bwd(c).total);
+  w.total = off;
+  return w;
+}
+
+// one-expert configuration for the dense layers' gradient GEMMs: rows tokens, widths in -> out
+moe_config dense_cfg(const moe_config& c, long long rows, int in, int out) {
+  moe_config g = c;
+  g.E = 1;
+  g.G = 1;
+  g.C = (int)rows;
+  g.M = in;
+  g.H = out;
+  return g;
+}
+
+// gradients of out = Attention(u): dout [N,M] -> du [N,M], dwqkv [M,3A], dwo_att [A,M]
+int attention_bwd_impl(const moe_config& c, const moe_encoder_dims& d, const void* u,
+                       const void* wqkv, const void* wo_att, const void* qkv, const void* ctx,
+                       const float* lse, const void* dout, void* du, void* dwqkv, void* dwo_att,
+                       void* dqkv, void* dctx, float* dvec, hipStream_t st) {
+  const long long N = (long long)c.G * c.S;
+  const int A = d.heads * d.d;
+  // out = ctx . wo_att
+  int rc = moe::launch_expert_wgrad2(dense_cfg(c, N, c.M, A), ctx, dout, dwo_att, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_expert_dgrad1(dense_cfg(c, N, A, c.M), dout, wo_att, dctx, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_attention_core_bwd(c.act_dtype, qkv, ctx, dctx, lse, dqkv, dvec, d.B, d.L, d.heads,
+                                      d.d, st);
+  if (rc != MOE_OK) return rc;
+  // qkv = u . wqkv
+  rc = moe::launch_expert_wgrad1(dense_cfg(c, N, c.M, 3 * A), u, dqkv, dwqkv, st);
+  if (rc != MOE_OK) return rc;
+  return moe::launch_expert_dgrad1(dense_cfg(c, N, c.M, 3 * A), dqkv, wqkv, du, st);
 }
 
 }  // namespace
@@ -428,8 +503,9 @@ int moe_self_attention(const moe_config* cfg, const moe_encoder_dims* dims, cons
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
   if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
   if (ws_bytes < carve_att(*cfg, *dims).total) return MOE_EWORKSPACE;
-  return attention_impl(*cfg, *dims, u, wqkv, wo_att, out, static_cast<char*>(ws),
-                        static_cast<hipStream_t>(stream));
+  const AttentionWs aw = carve_att(*cfg, *dims);
+  return attention_impl(*cfg, *dims, u, wqkv, wo_att, out, static_cast<char*>(ws) + aw.qkv,
+                        static_cast<char*>(ws) + aw.ctx, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int moe_dense_ffn(const moe_config* cfg, const void* u, const void* w1, const void* w2, void* h_ws,
@@ -469,7 +545,9 @@ int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims
   // layer 1: a = x + Attention_1(LN_1(x)); b = a + FFN(LN_2(a))
   rc = moe::launch_add_layer_norm(dt, x, nullptr, w->ln_gamma[0], w->ln_beta[0], nullptr, norm, N, cfg->M, st);
   if (rc != MOE_OK) return rc;
-  rc = attention_impl(*cfg, *dims, norm, w->wqkv[0], w->wo_att[0], sub, base + e.att, st);
+  const AttentionWs aw = carve_att(*cfg, *dims);
+  rc = attention_impl(*cfg, *dims, norm, w->wqkv[0], w->wo_att[0], sub, base + e.att + aw.qkv,
+                      base + e.att + aw.ctx, nullptr, st);
   if (rc != MOE_OK) return rc;
   rc = moe::launch_add_layer_norm(dt, x, sub, w->ln_gamma[1], w->ln_beta[1], a, norm, N, cfg->M, st);
   if (rc != MOE_OK) return rc;
@@ -480,7 +558,8 @@ int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims
   // layer 2: c = b + Attention_2(LN_3(b)); y = c + MoE(LN_4(c))
   rc = moe::launch_add_layer_norm(dt, a, sub, w->ln_gamma[2], w->ln_beta[2], b, norm, N, cfg->M, st);
   if (rc != MOE_OK) return rc;
-  rc = attention_impl(*cfg, *dims, norm, w->wqkv[1], w->wo_att[1], sub, base + e.att, st);
+  rc = attention_impl(*cfg, *dims, norm, w->wqkv[1], w->wo_att[1], sub, base + e.att + aw.qkv,
+                      base + e.att + aw.ctx, nullptr, st);
   if (rc != MOE_OK) return rc;
   rc = moe::launch_add_layer_norm(dt, b, sub, w->ln_gamma[3], w->ln_beta[3], c, norm, N, cfg->M, st);
   if (rc != MOE_OK) return rc;
@@ -488,6 +567,141 @@ int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims
                     stream, nullptr, false);
   if (rc != MOE_OK) return rc;
   return moe::launch_add_rows(dt, c, sub, y, N * cfg->M, st);
+}
+
+int moe_encoder_train_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims, size_t* bytes) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve_enc_train(*cfg, *dims).total;
+  return MOE_OK;
+}
+
+int moe_encoder_backward_workspace_bytes(const moe_config* cfg, const moe_encoder_dims* dims,
+                                         size_t* bytes) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve_enc_bwd(*cfg, *dims).total;
+  return MOE_OK;
+}
+
+int moe_encoder_pair_forward_train(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                                   const moe_encoder_weights* w, const float* u, void* y, float* aux,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (w == nullptr) return MOE_EINVAL;
+  const void* req[] = {x, u, y, aux, ws, w->wqkv[0], w->wqkv[1], w->wo_att[0], w->wo_att[1], w->w1,
+                       w->w2, w->wg, w->wi, w->wo, w->ln_gamma[0], w->ln_gamma[1], w->ln_gamma[2],
+                       w->ln_gamma[3], w->ln_beta[0], w->ln_beta[1], w->ln_beta[2], w->ln_beta[3]};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  const EncoderTrainWs e = carve_enc_train(*cfg, *dims);
+  if (ws_bytes < e.total) return MOE_EWORKSPACE;
+  char* base = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long long N = (long long)cfg->G * cfg->S;
+  const int dt = cfg->act_dtype;
+  void *sub = base + e.sub, *a = base + e.a, *b = base + e.b, *c = base + e.c;
+  auto lse = [&](int i) { return reinterpret_cast<float*>(base + e.lse[i]); };
+  rc = moe::launch_add_layer_norm(dt, x, nullptr, w->ln_gamma[0], w->ln_beta[0], nullptr, base + e.n[0], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = attention_impl(*cfg, *dims, base + e.n[0], w->wqkv[0], w->wo_att[0], sub, base + e.qkv[0],
+                      base + e.ctx[0], lse(0), st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_add_layer_norm(dt, x, sub, w->ln_gamma[1], w->ln_beta[1], a, base + e.n[1], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = dense_gemm(*cfg, N, cfg->M, cfg->H, true, base + e.n[1], w->w1, base + e.hden, st);
+  if (rc != MOE_OK) return rc;
+  rc = dense_gemm(*cfg, N, cfg->H, cfg->M, false, base + e.hden, w->w2, sub, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_add_layer_norm(dt, a, sub, w->ln_gamma[2], w->ln_beta[2], b, base + e.n[2], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = attention_impl(*cfg, *dims, base + e.n[2], w->wqkv[1], w->wo_att[1], sub, base + e.qkv[1],
+                      base + e.ctx[1], lse(1), st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_add_layer_norm(dt, b, sub, w->ln_gamma[3], w->ln_beta[3], c, base + e.n[3], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  rc = forward_impl(cfg, base + e.n[3], w->wg, u, w->wi, w->wo, sub, aux, base + e.moe,
+                    carve(*cfg).total, stream, nullptr, true);
+  if (rc != MOE_OK) return rc;
+  return moe::launch_add_rows(dt, c, sub, y, N * cfg->M, st);
+}
+
+int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
+                              const moe_encoder_weights* w, const void* dy, const float* daux,
+                              const void* fwd_ws, size_t fwd_ws_bytes, void* dx,
+                              const moe_encoder_grads* g, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if ((rc = check_dims(cfg, dims)) != MOE_OK) return rc;
+  if (w == nullptr || g == nullptr) return MOE_EINVAL;
+  const void* req[] = {x, dy, daux, fwd_ws, dx, ws, w->wqkv[0], w->wqkv[1], w->wo_att[0], w->wo_att[1],
+                       w->w1, w->w2, w->wg, w->wi, w->wo, w->ln_gamma[0], w->ln_gamma[1],
+                       w->ln_gamma[2], w->ln_gamma[3], g->wqkv[0], g->wqkv[1], g->wo_att[0],
+                       g->wo_att[1], g->w1, g->w2, g->wg, g->wi, g->wo, g->ln_gamma[0], g->ln_gamma[1],
+                       g->ln_gamma[2], g->ln_gamma[3], g->ln_beta[0], g->ln_beta[1], g->ln_beta[2],
+                       g->ln_beta[3]};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(fwd_ws) & 255u) != 0) return MOE_EINVAL;
+  const EncoderTrainWs e = carve_enc_train(*cfg, *dims);
+  const EncoderBwdWs bw = carve_enc_bwd(*cfg, *dims);
+  if (fwd_ws_bytes < e.total || ws_bytes < bw.total) return MOE_EWORKSPACE;
+  const char* f = static_cast<const char*>(fwd_ws);
+  char* base = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long long N = (long long)cfg->G * cfg->S;
+  const int dt = cfg->act_dtype;
+  void *g0 = base + bw.g[0], *g1 = base + bw.g[1], *dn = base + bw.dn;
+  float* partial = reinterpret_cast<float*>(base + bw.partial);
+  float* dvec = reinterpret_cast<float*>(base + bw.dvec);
+  auto lse = [&](int i) { return reinterpret_cast<const float*>(f + e.lse[i]); };
+
+  // y = c + MoE(n4): the MoE layer's gradients; dn = d L / d n4
+  rc = moe_backward(cfg, f + e.n[3], w->wg, w->wi, w->wo, dy, daux, f + e.moe, carve(*cfg).total, dn,
+                    g->wg, g->wi, g->wo, base + bw.moe, carve_bwd(*cfg).total, stream);
+  if (rc != MOE_OK) return rc;
+  // g0 = d L / d c = dy + LN4'(dn)
+  rc = moe::launch_layer_norm_bwd(dt, f + e.c, dn, w->ln_gamma[3], dy, g0, partial, g->ln_gamma[3],
+                                  g->ln_beta[3], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  // c = b + Attention_2(n3)
+  rc = attention_bwd_impl(*cfg, *dims, f + e.n[2], w->wqkv[1], w->wo_att[1], f + e.qkv[1],
+                          f + e.ctx[1], lse(1), g0, dn, g->wqkv[1], g->wo_att[1], base + bw.dqkv,
+                          base + bw.dctx, dvec, st);
+  if (rc != MOE_OK) return rc;
+  rc = moe::launch_layer_norm_bwd(dt, f + e.b, dn, w->ln_gamma[2], g0, g1, partial, g->ln_gamma[2],
+                                  g->ln_beta[2], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  // b = a + relu(n2 w1) w2
+  {
+    const moe_config fc = dense_cfg(*cfg, N, cfg->M, cfg->H);
+    rc = moe::launch_expert_wgrad2(fc, f + e.hden, g1, g->w2, st);
+    if (rc != MOE_OK) return rc;
+    rc = moe::launch_expert_dgrad2(fc, g1, w->w2, f + e.hden, nullptr, base + bw.dhden, st);
+    if (rc != MOE_OK) return rc;
+    rc = moe::launch_expert_wgrad1(fc, f + e.n[1], base + bw.dhden, g->w1, st);
+    if (rc != MOE_OK) return rc;
+    rc = moe::launch_expert_dgrad1(fc, base + bw.dhden, w->w1, dn, st);
+    if (rc != MOE_OK) return rc;
+  }
+  rc = moe::launch_layer_norm_bwd(dt, f + e.a, dn, w->ln_gamma[1], g1, g0, partial, g->ln_gamma[1],
+                                  g->ln_beta[1], N, cfg->M, st);
+  if (rc != MOE_OK) return rc;
+  // a = x + Attention_1(n1)
+  rc = attention_bwd_impl(*cfg, *dims, f + e.n[0], w->wqkv[0], w->wo_att[0], f + e.qkv[0],
+                          f + e.ctx[0], lse(0), g0, dn, g->wqkv[0], g->wo_att[0], base + bw.dqkv,
+                          base + bw.dctx, dvec, st);
+  if (rc != MOE_OK) return rc;
+  return moe::launch_layer_norm_bwd(dt, x, dn, w->ln_gamma[0], g0, dx, partial, g->ln_gamma[0],
+                                    g->ln_beta[0], N, cfg->M, st);
 }
 
 }  // extern "C"

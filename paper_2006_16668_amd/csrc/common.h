@@ -179,8 +179,21 @@ int launch_add_layer_norm(int act_dtype, const void* x, const void* delta, const
                           hipStream_t st);
 int launch_add_rows(int act_dtype, const void* a, const void* b, void* y, long long elems,
                     hipStream_t st);
-int launch_attention_core(int act_dtype, const void* qkv, void* ctx, long long B, int L, int heads,
-                          int d, hipStream_t st);
+// lse: NULL, or [B*heads*L] fp32 that receives log sum_k exp(score) per query row (training)
+int launch_attention_core(int act_dtype, const void* qkv, void* ctx, float* lse, long long B, int L,
+                          int heads, int d, hipStream_t st);
+
+// backward of the encoder sub-layers (encoder_bwd.hip)
+//   ds = dres (may be NULL) + d LN(s) / d s applied to dn; dgamma, dbeta [M]; partial:
+//   layer_norm_bwd_parts(rows) * 2 * M floats of scratch.  dx may alias dres.
+int layer_norm_bwd_parts(long long rows);
+int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const float* gamma,
+                          const void* dres, void* dx, float* partial, float* dgamma, float* dbeta,
+                          long long rows, int M, hipStream_t st);
+//   dqkv [B*L, 3*heads*d] from qkv, ctx, dctx [B*L, heads*d] and lse; dvec: [B*heads*L] scratch
+int launch_attention_core_bwd(int act_dtype, const void* qkv, const void* ctx, const void* dctx,
+                              const float* lse, void* dqkv, float* dvec, long long B, int L,
+                              int heads, int d, hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
 

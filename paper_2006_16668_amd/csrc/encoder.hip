@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256) void add_rows_kernel(const uint4* __restrict__
 // One wavefront per (sequence, head, query).  Scores of the whole row sit in LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void attention_rows_kernel(
-    const T* __restrict__ qkv, T* __restrict__ ctx, int L, int heads, int d, long long queries) {
+    const T* __restrict__ qkv, T* __restrict__ ctx, float* __restrict__ lse, int L, int heads, int d,
+    long long queries) {
   extern __shared__ float att_smem[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float* sc = att_smem + (size_t)wave * (L + d);        // [L] scores, then [d] the query row
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(
     sum += p;
   }
   sum = wave_sum(sum);
+  if (lse != nullptr && lane == 0) lse[id] = mx + logf(sum);   // log sum_k exp(score), for the backward pass
   __builtin_amdgcn_wave_barrier();
   const float inv = 1.0f / sum;
   T* out = ctx + ((size_t)b * L + l) * A + (size_t)h * d;
@@ -160,7 +162,8 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
-    const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, int L, int heads) {
+    const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int L,
+    int heads) {
   constexpr int KS = D / 16;                 // MFMA steps over d for the scores
   constexpr int DT = D / 32;                 // 32-row tiles of O^T
   // Row pitches of the staged blocks, chosen for the 64 LDS banks: the 16-byte K reads of 16
@@ -303,6 +306,9 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
 #undef MOE_ATT_STORE_KV
   // o[dt][i]: d = 32 dt + 8 (i/4) + 4 hf + i%4 of query r: four consecutive d per 8-byte store
   const float inv = 1.0f / l_run;
+  // row statistic for the backward pass: log sum_k exp(score) in natural-log units
+  if (lse != nullptr && hf == 0)
+    lse[(size_t)bh * L + qb * 128 + wave * 32 + r] = (m_run + log2f(l_run)) * 0.6931471805599453f;
   bf16_t* orow = ctx + ((size_t)b * L + qb * 128 + wave * 32 + r) * A + (size_t)h * D;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -359,17 +365,17 @@ int launch_add_rows(int act_dtype, const void* a, const void* b, void* y, long l
 }
 
 // ctx [B*L, heads*d] from qkv [B*L, 3*heads*d]
-int launch_attention_core(int act_dtype, const void* qkv, void* ctx, long long B, int L, int heads,
-                          int d, hipStream_t st) {
+int launch_attention_core(int act_dtype, const void* qkv, void* ctx, float* lse, long long B, int L,
+                          int heads, int d, hipStream_t st) {
   if (act_dtype == MOE_BF16 && (d == 64 || d == 128) && L % 128 == 0) {
     const long long blocks = B * heads * (L / 128);
     if (blocks > 0x7fffffffLL) return MOE_EUNSUPPORTED;
     if (d == 64)
       hipLaunchKernelGGL(attention_mfma_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st,
-                         static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), L, heads);
+                         static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), lse, L, heads);
     else
       hipLaunchKernelGGL(attention_mfma_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st,
-                         static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), L, heads);
+                         static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), lse, L, heads);
     return check_launch();
   }
   const size_t shm = (size_t)4 * (L + d) * sizeof(float);
@@ -379,10 +385,10 @@ int launch_attention_core(int act_dtype, const void* qkv, void* ctx, long long B
   if (blocks > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   if (act_dtype == MOE_F32)
     hipLaunchKernelGGL(attention_rows_kernel<float>, dim3((unsigned)blocks), dim3(256), shm, st,
-                       static_cast<const float*>(qkv), static_cast<float*>(ctx), L, heads, d, queries);
+                       static_cast<const float*>(qkv), static_cast<float*>(ctx), lse, L, heads, d, queries);
   else
     hipLaunchKernelGGL(attention_rows_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), shm, st,
-                       static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), L, heads, d, queries);
+                       static_cast<const bf16_t*>(qkv), static_cast<bf16_t*>(ctx), lse, L, heads, d, queries);
   return check_launch();
 }
 
