@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_gfx950.so")
 SOURCES = ["api.hip", "gate.hip", "dispatch_combine.hip", "expert_gemm.hip", "backward.hip", "encoder.hip",
-           "gemm_f32.hip", "encoder_bwd.hip"]
+           "gemm_f32.hip", "encoder_bwd.hip",
+           "attention_bwd_mfma.hip"]
 # packed-fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -191,6 +191,11 @@ int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const fl
                           const void* dres, void* dx, float* partial, float* dgamma, float* dbeta,
                           long long rows, int M, hipStream_t st);
 //   dqkv [B*L, 3*heads*d] from qkv, ctx, dctx [B*L, heads*d] and lse; dvec: [B*heads*L] scratch
+// MFMA form (attention_bwd_mfma.hip): bf16, d = 64 or 128, L % 128 == 0
+bool attention_bwd_mfma_ok(int act_dtype, int L, int d);
+int launch_attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse,
+                              void* dqkv, float* dvec, long long B, int L, int heads, int d,
+                              hipStream_t st);
 int launch_attention_core_bwd(int act_dtype, const void* qkv, const void* ctx, const void* dctx,
                               const float* lse, void* dqkv, float* dvec, long long B, int L,
                               int heads, int d, hipStream_t st);

@@ -278,6 +278,8 @@ int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const fl
 int launch_attention_core_bwd(int act_dtype, const void* qkv, const void* ctx, const void* dctx,
                               const float* lse, void* dqkv, float* dvec, long long B, int L,
                               int heads, int d, hipStream_t st) {
+  if (attention_bwd_mfma_ok(act_dtype, L, d))
+    return launch_attention_bwd_mfma(qkv, ctx, dctx, lse, dqkv, dvec, B, L, heads, d, st);
   const long long rows = B * heads * L;
   const size_t lds = (size_t)4 * (2 * L + 2 * d) * sizeof(float);
   if (lds > 64 * 1024 || (rows + 3) / 4 > 0x7fffffffLL) return MOE_EUNSUPPORTED;

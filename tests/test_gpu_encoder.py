@@ -24,6 +24,9 @@ CASES = [
     (MoEConfig("enc_flash64", G=2, S=512, M=256, H=512, E=8, C=128, act_dtype="bf16", seed=51), 4, 256, 4, 64),
     (MoEConfig("enc_flash128", G=2, S=256, M=256, H=256, E=4, C=128, act_dtype="bf16", seed=52), 2, 256, 2, 128),
     (MoEConfig("enc_long", G=1, S=1024, M=128, H=256, E=4, C=512, act_dtype="bf16", seed=53), 1, 1024, 2, 64),
+    # paper-like attention shape (sequences of 1024, key/value dimension 128) at a size the
+    # oracle finishes in seconds: several query / key blocks per head, several row tiles per GEMM
+    (MoEConfig("enc_mid", G=4, S=1024, M=512, H=1024, E=8, C=256, act_dtype="bf16", seed=56), 4, 1024, 4, 128),
     (MoEConfig("enc_plain_bf16", G=3, S=40, M=72, H=136, E=5, C=20, act_dtype="bf16", seed=54), 4, 30, 3, 24),
     (MoEConfig("enc_f32", G=2, S=48, M=32, H=64, E=4, C=24, act_dtype="f32", seed=55), 3, 32, 2, 16),
 ]
