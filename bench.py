@@ -197,7 +197,20 @@ def time_encoder(moe, cfg, sh, inp, K, W, peak):
     ffn = timed(lambda: moe.moe_dense_ffn(sh, inp.x, w["w1"], w["w2"], hden, t))
     ln = timed(lambda: moe.moe_add_layer_norm(sh, inp.x, t, w["ln_gamma"][0], w["ln_beta"][0], y, t))
     att_flops = 2.0 * cfg.N * cfg.M * 3 * A + 2.0 * cfg.N * A * cfg.M + 4.0 * cfg.N * L * A
+    # training: forward that keeps the activations, then the backward pass of both layers
+    from workloads import make_upstream
+    dy, daux = make_upstream(cfg, device=dev)
+    del ws, aws, hden
+    fws = torch.empty(moe.moe_encoder_train_workspace_bytes(sh, dims), dtype=torch.uint8, device=dev)
+    bws = torch.empty(moe.moe_encoder_backward_workspace_bytes(sh, dims), dtype=torch.uint8, device=dev)
+    grads = {k: ([torch.empty_like(v) for v in weights[k]] if isinstance(weights[k], (list, tuple))
+                 else torch.empty_like(weights[k])) for k in weights}
+    dx = torch.empty_like(inp.x)
+    train_fwd = timed(lambda: moe.moe_encoder_pair_forward_train(sh, dims, inp.x, weights, inp.u, y, aux, fws))
+    bwd = timed(lambda: moe.moe_encoder_pair_backward(sh, dims, inp.x, weights, dy, daux, fws, dx, grads, bws))
     return {"ms_per_step": pair, "tokens_per_s": cfg.N / (pair * 1e-3),
+            "train_forward_ms_per_step": train_fwd, "backward_ms_per_step": bwd,
+            "train_tokens_per_s": cfg.N / ((train_fwd + bwd) * 1e-3),
             "dims": {"sequences": dims.B, "length": L, "heads": heads, "d": d},
             "self_attention_ms": att, "self_attention_mfma_frac": att_flops / (att * 1e-3) / 1e12 / peak,
             "dense_ffn_ms": ffn, "dense_ffn_mfma_frac": 4.0 * cfg.N * cfg.M * cfg.H / (ffn * 1e-3) / 1e12 / peak,

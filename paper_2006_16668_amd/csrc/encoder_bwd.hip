@@ -111,15 +111,26 @@ __global__ __launch_bounds__(256) void layer_norm_bwd_kernel(
     }
 }
 
-// dgamma[m] = sum_p partial[p][0][m], dbeta[m] = sum_p partial[p][1][m]
+// dgamma[m] = sum_p partial[p][0][m], dbeta[m] = sum_p partial[p][1][m]: a block owns 16 of the
+// 2 M columns, its 16 groups of 16 threads each sum every 16th partial row, LDS adds the groups
+// in a fixed order (bit-reproducible)
 __global__ __launch_bounds__(256) void layer_norm_param_reduce_kernel(
     const float* __restrict__ partial, int parts, int M, float* __restrict__ dgamma,
     float* __restrict__ dbeta) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= 2 * M) return;
+  __shared__ float red[16][17];
+  const int c = threadIdx.x & 15, pl = threadIdx.x >> 4;
+  const int i = blockIdx.x * 16 + c;
   float acc = 0.f;
-  for (int p = 0; p < parts; ++p) acc += partial[(size_t)p * 2 * M + i];
-  if (i < M) dgamma[i] = acc; else dbeta[i - M] = acc;
+  if (i < 2 * M)
+    for (int p = pl; p < parts; p += 16) acc += partial[(size_t)p * 2 * M + i];
+  red[pl][c] = acc;
+  __syncthreads();
+  if (pl == 0 && i < 2 * M) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t += red[k][c];
+    if (i < M) dgamma[i] = t; else dbeta[i - M] = t;
+  }
 }
 
 // ---------------------------------------------------------------- attention core, plain form
@@ -269,7 +280,7 @@ int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const fl
 #undef MOE_LNB_CASE
   int rc = check_launch();
   if (rc != MOE_OK) return rc;
-  hipLaunchKernelGGL(layer_norm_param_reduce_kernel, dim3((unsigned)((2 * M + 255) / 256)), dim3(256),
+  hipLaunchKernelGGL(layer_norm_param_reduce_kernel, dim3((unsigned)((2 * M + 15) / 16)), dim3(256),
                      0, st, partial, parts, M, dgamma, dbeta);
   return check_launch();
 }
