@@ -135,3 +135,63 @@ def test_encoder_backward_is_reproducible_and_checks_arguments():
         aux = torch.empty(cfg.G, dtype=torch.float32, device=DEV)
         moe.moe_encoder_pair_forward_train(sh, dims, inp.x, weights, inp.u, y, aux, small)
     assert ei.value.status == -3
+
+
+def test_encoder_training_step_replays_from_a_hip_graph():
+    """Forward-train + backward of the pair only enqueue kernels on the caller's stream, so the
+    step can be captured once and replayed on fresh inputs in the captured buffers; every
+    replay must equal the eager calls bit for bit."""
+    cfg, B, L, heads, d = CASES[0]
+    dims = moe.EncoderDims(B, L, heads, d)
+    sh = shape_of(cfg)
+    sets = []
+    for k in range(2):
+        c = cfg.with_(seed=cfg.seed + 7 * k)
+        sets.append((make_inputs(c, device=DEV), make_encoder_weights(c, heads, d, device=DEV),
+                     make_upstream(c, device=DEV)))
+    inp0, w0, (dy0, daux0) = sets[0]
+    x, u = inp0.x.clone(), inp0.u.clone()
+    weights = {k: ([t.clone() for t in v] if isinstance(v, list) else v.clone()) for k, v in w0.items()}
+    weights.update(wg=inp0.wg.clone(), wi=inp0.wi.clone(), wo=inp0.wo.clone())
+    dy, daux = dy0.clone(), daux0.clone()
+    y = torch.empty_like(x)
+    aux = torch.empty(cfg.G, dtype=torch.float32, device=DEV)
+    grads = {k: ([torch.empty_like(t) for t in v] if isinstance(v, list) else torch.empty_like(v))
+             for k, v in weights.items()}
+    dx = torch.empty_like(x)
+    fws = torch.empty(moe.moe_encoder_train_workspace_bytes(sh, dims), dtype=torch.uint8, device=DEV)
+    bws = torch.empty(moe.moe_encoder_backward_workspace_bytes(sh, dims), dtype=torch.uint8, device=DEV)
+
+    def step():
+        moe.moe_encoder_pair_forward_train(sh, dims, x, weights, u, y, aux, fws)
+        moe.moe_encoder_pair_backward(sh, dims, x, weights, dy, daux, fws, dx, grads, bws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                        # first call outside capture: one-time kernel attributes
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for k in (1, 0, 1):
+        inp, w, (dyk, dauxk) = sets[k]
+        x.copy_(inp.x); u.copy_(inp.u); dy.copy_(dyk); daux.copy_(dauxk)
+        for name, v in w.items():
+            if isinstance(v, list):
+                for dst, src in zip(weights[name], v):
+                    dst.copy_(src)
+            else:
+                weights[name].copy_(v)
+        weights["wg"].copy_(inp.wg); weights["wi"].copy_(inp.wi); weights["wo"].copy_(inp.wo)
+        graph.replay()
+        torch.cuda.synchronize()
+        y_e, aux_e, dx_e, g_e = _gpu_backward(cfg, dims, inp, w, dyk, dauxk)      # eager, own buffers
+        assert torch.equal(y, y_e) and torch.equal(aux, aux_e) and torch.equal(dx, dx_e), k
+        for name in ("w1", "w2", "wg", "wi", "wo"):
+            assert torch.equal(grads[name], g_e[name]), (k, name)
+        for i in range(2):
+            assert torch.equal(grads["wqkv"][i], g_e["wqkv"][i]) and torch.equal(grads["wo_att"][i], g_e["wo_att"][i])
+        for i in range(4):
+            assert torch.equal(grads["ln_gamma"][i], g_e["ln_gamma"][i]) and torch.equal(grads["ln_beta"][i], g_e["ln_beta"][i])
