@@ -216,7 +216,7 @@ def time_encoder(moe, cfg, sh, inp, K, W, peak):
             "dense_ffn_ms": ffn, "dense_ffn_mfma_frac": 4.0 * cfg.N * cfg.M * cfg.H / (ffn * 1e-3) / 1e12 / peak,
             "add_layer_norm_ms": ln,
             "add_layer_norm_hbm_frac": 4.0 * cfg.N * cfg.M * inp.x.element_size() / (ln * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "note": "x -> attention + dense FFN layer -> attention + MoE layer (forward); not part of value"}
+            "note": "x -> attention + dense FFN layer -> attention + MoE layer, forward and backward; not part of value"}
 
 
 def time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak):
