@@ -221,7 +221,7 @@ EncoderTrainWs carve_enc_train(const moe_config& c, const moe_encoder_dims& d) {
   return w;
 }
 
-struct EncoderBwdWs { size_t g[2], dn, dqkv, dctx, dhden, dvec, partial, moe, total; };
+struct EncoderBwdWs { size_t g[2], dn, dqkv, dctx, dhden, dvec, partial, wpart, moe, total; };
 EncoderBwdWs carve_enc_bwd(const moe_config& c, const moe_encoder_dims& d) {
   const size_t N = (size_t)c.G * c.S, A = (size_t)d.heads * d.d;
   const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
@@ -236,6 +236,15 @@ EncoderBwdWs carve_enc_bwd(const moe_config& c, const moe_encoder_dims& d) {
   w.dhden = take(N * c.H * elt);
   w.dvec = take((size_t)d.B * d.heads * d.L * sizeof(float));
   w.partial = take((size_t)moe::layer_norm_bwd_parts((long long)N) * 2 * c.M * sizeof(float));
+  // token ranges of the dense weight gradients (the largest of the four shapes)
+  size_t wp = moe::dense_wgrad_partial_bytes(c.act_dtype, (long long)N, (int)A, c.M);
+  const size_t wp2 = moe::dense_wgrad_partial_bytes(c.act_dtype, (long long)N, c.M, 3 * (int)A);
+  const size_t wp3 = moe::dense_wgrad_partial_bytes(c.act_dtype, (long long)N, c.M, c.H);
+  const size_t wp4 = moe::dense_wgrad_partial_bytes(c.act_dtype, (long long)N, c.H, c.M);
+  wp = wp > wp2 ? wp : wp2;
+  wp = wp > wp3 ? wp : wp3;
+  wp = wp > wp4 ? wp : wp4;
+  w.wpart = take(wp);
   w.moe = take(carve_bwd(c).total);
   w.total = off;
   return w;
@@ -256,11 +265,11 @@ moe_config dense_cfg(const moe_config& c, long long rows, int in, int out) {
 int attention_bwd_impl(const moe_config& c, const moe_encoder_dims& d, const void* u,
                        const void* wqkv, const void* wo_att, const void* qkv, const void* ctx,
                        const float* lse, const void* dout, void* du, void* dwqkv, void* dwo_att,
-                       void* dqkv, void* dctx, float* dvec, hipStream_t st) {
+                       void* dqkv, void* dctx, float* dvec, float* wpart, hipStream_t st) {
   const long long N = (long long)c.G * c.S;
   const int A = d.heads * d.d;
   // out = ctx . wo_att
-  int rc = moe::launch_expert_wgrad2(dense_cfg(c, N, c.M, A), ctx, dout, dwo_att, st);
+  int rc = moe::launch_dense_wgrad(c, N, A, c.M, ctx, dout, dwo_att, wpart, st);
   if (rc != MOE_OK) return rc;
   rc = moe::launch_expert_dgrad1(dense_cfg(c, N, A, c.M), dout, wo_att, dctx, st);
   if (rc != MOE_OK) return rc;
@@ -268,7 +277,7 @@ int attention_bwd_impl(const moe_config& c, const moe_encoder_dims& d, const voi
                                       d.d, st);
   if (rc != MOE_OK) return rc;
   // qkv = u . wqkv
-  rc = moe::launch_expert_wgrad1(dense_cfg(c, N, c.M, 3 * A), u, dqkv, dwqkv, st);
+  rc = moe::launch_dense_wgrad(c, N, c.M, 3 * A, u, dqkv, dwqkv, wpart, st);
   if (rc != MOE_OK) return rc;
   return moe::launch_expert_dgrad1(dense_cfg(c, N, c.M, 3 * A), dqkv, wqkv, du, st);
 }
@@ -662,6 +671,7 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
   void *g0 = base + bw.g[0], *g1 = base + bw.g[1], *dn = base + bw.dn;
   float* partial = reinterpret_cast<float*>(base + bw.partial);
   float* dvec = reinterpret_cast<float*>(base + bw.dvec);
+  float* wpart = reinterpret_cast<float*>(base + bw.wpart);
   auto lse = [&](int i) { return reinterpret_cast<const float*>(f + e.lse[i]); };
 
   // y = c + MoE(n4): the MoE layer's gradients; dn = d L / d n4
@@ -675,7 +685,7 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
   // c = b + Attention_2(n3)
   rc = attention_bwd_impl(*cfg, *dims, f + e.n[2], w->wqkv[1], w->wo_att[1], f + e.qkv[1],
                           f + e.ctx[1], lse(1), g0, dn, g->wqkv[1], g->wo_att[1], base + bw.dqkv,
-                          base + bw.dctx, dvec, st);
+                          base + bw.dctx, dvec, wpart, st);
   if (rc != MOE_OK) return rc;
   rc = moe::launch_layer_norm_bwd(dt, f + e.b, dn, w->ln_gamma[2], g0, g1, partial, g->ln_gamma[2],
                                   g->ln_beta[2], N, cfg->M, st);
@@ -683,11 +693,11 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
   // b = a + relu(n2 w1) w2
   {
     const moe_config fc = dense_cfg(*cfg, N, cfg->M, cfg->H);
-    rc = moe::launch_expert_wgrad2(fc, f + e.hden, g1, g->w2, st);
+    rc = moe::launch_dense_wgrad(*cfg, N, cfg->H, cfg->M, f + e.hden, g1, g->w2, wpart, st);
     if (rc != MOE_OK) return rc;
     rc = moe::launch_expert_dgrad2(fc, g1, w->w2, f + e.hden, nullptr, base + bw.dhden, st);
     if (rc != MOE_OK) return rc;
-    rc = moe::launch_expert_wgrad1(fc, f + e.n[1], base + bw.dhden, g->w1, st);
+    rc = moe::launch_dense_wgrad(*cfg, N, cfg->M, cfg->H, f + e.n[1], base + bw.dhden, g->w1, wpart, st);
     if (rc != MOE_OK) return rc;
     rc = moe::launch_expert_dgrad1(fc, base + bw.dhden, w->w1, dn, st);
     if (rc != MOE_OK) return rc;
@@ -698,7 +708,7 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
   // a = x + Attention_1(n1)
   rc = attention_bwd_impl(*cfg, *dims, f + e.n[0], w->wqkv[0], w->wo_att[0], f + e.qkv[0],
                           f + e.ctx[0], lse(0), g0, dn, g->wqkv[0], g->wo_att[0], base + bw.dqkv,
-                          base + bw.dctx, dvec, st);
+                          base + bw.dctx, dvec, wpart, st);
   if (rc != MOE_OK) return rc;
   return moe::launch_layer_norm_bwd(dt, x, dn, w->ln_gamma[0], g0, dx, partial, g->ln_gamma[0],
                                     g->ln_beta[0], N, cfg->M, st);

@@ -191,6 +191,12 @@ int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const fl
                           const void* dres, void* dx, float* partial, float* dgamma, float* dbeta,
                           long long rows, int M, hipStream_t st);
 //   dqkv [B*L, 3*heads*d] from qkv, ctx, dctx [B*L, heads*d] and lse; dvec: [B*heads*L] scratch
+// dW [in,out] = X^T dY over rows tokens (X [rows,in], dY [rows,out]); partial: scratch of
+// dense_wgrad_partial_bytes() for the token ranges of the split (may be NULL: no split)
+int dense_wgrad_splits(int act_dtype, long long rows, int in, int out);
+size_t dense_wgrad_partial_bytes(int act_dtype, long long rows, int in, int out);
+int launch_dense_wgrad(const moe_config& c, long long rows, int in, int out, const void* X,
+                       const void* dY, void* dW, float* partial, hipStream_t st);
 // MFMA form (attention_bwd_mfma.hip): bf16, d = 64 or 128, L % 128 == 0
 bool attention_bwd_mfma_ok(int act_dtype, int L, int d);
 int launch_attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse,

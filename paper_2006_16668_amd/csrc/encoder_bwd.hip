@@ -248,7 +248,65 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_rows_kernel(
   }
 }
 
+// out[i] = sum_s partial[s][i] (fixed order), rounded once to bf16; 8 elements per thread
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
+                                                            int splits, long long elems,
+                                                            uint4* __restrict__ out) {
+  const long long v = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (v * 8 >= elems) return;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int sp = 0; sp < splits; ++sp) {
+    const float4* p = reinterpret_cast<const float4*>(partial + (size_t)sp * elems + v * 8);
+    const float4 a = p[0], b = p[1];
+    acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+    acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+  }
+  out[v] = Vec16<bf16_t>::pack(acc);
+}
+
 }  // namespace
+
+// Weight gradient of a dense layer, dW [in,out] = X^T dY over `rows` tokens.  Its output has
+// few 256 x 256 tiles (in/256 * out/256) but a very long K (the tokens), so the persistent GEMM
+// alone would leave most compute units idle: the tokens are cut into `splits` ranges that run
+// as a batch with fp32 results, and one pass adds the ranges in order and rounds once.
+// The plan picks the number of ranges that fills the 256 compute units best.
+int dense_wgrad_splits(int act_dtype, long long rows, int in, int out) {
+  if (act_dtype != MOE_BF16 || in % 256 != 0 || out % 256 != 0) return 1;
+  const long long tiles = (long long)(in / 256) * (out / 256);
+  int best = 1;
+  double best_fill = 0.0;
+  for (int sp = 1; sp <= 16; sp *= 2) {
+    if (rows % sp != 0 || (rows / sp) % 32 != 0 || rows / sp < 512) break;
+    if (!gemm_bf16_f32out_ok(in, out, (int)(rows / sp))) continue;
+    const long long t = tiles * sp;
+    const double fill = (double)t / (double)((t + 255) / 256 * 256);
+    if (fill > best_fill + 1e-9) { best_fill = fill; best = sp; }
+  }
+  return best;
+}
+
+size_t dense_wgrad_partial_bytes(int act_dtype, long long rows, int in, int out) {
+  const int sp = dense_wgrad_splits(act_dtype, rows, in, out);
+  return sp > 1 ? (size_t)sp * in * out * sizeof(float) : 0;
+}
+
+int launch_dense_wgrad(const moe_config& c, long long rows, int in, int out, const void* X,
+                       const void* dY, void* dW, float* partial, hipStream_t st) {
+  if (rows > 0x7fffffffLL) return MOE_EUNSUPPORTED;
+  const int sp = dense_wgrad_splits(c.act_dtype, rows, in, out);
+  if (sp <= 1 || partial == nullptr) {
+    moe_config g = c;
+    g.E = 1; g.G = 1; g.C = (int)rows; g.M = in; g.H = out;
+    return launch_expert_wgrad1(g, X, dY, dW, st);
+  }
+  const int rc = launch_gemm_bf16_f32out(true, X, dY, partial, sp, in, out, (int)(rows / sp), st);
+  if (rc != MOE_OK) return rc;
+  const long long elems = (long long)in * out;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((elems / 8 + 255) / 256)), dim3(256), 0, st,
+                     partial, sp, elems, static_cast<uint4*>(dW));
+  return check_launch();
+}
 
 int layer_norm_bwd_parts(long long rows) {
   const long long blocks = (rows + 3) / 4;
