@@ -21,7 +21,8 @@ namespace {
 
 // ---------------------------------------------------------------- layer normalisation
 // One wavefront per row, a wavefront walks rows wave, wave + waves, ...; its column sums of
-// dn * xhat and dn stay in registers and leave as one partial row per wavefront.
+// dn * xhat and dn stay in registers; the four wavefronts of a block add theirs in LDS (fixed
+// order) and the block leaves one partial row.
 template <typename T, int VPL>
 __global__ __launch_bounds__(256) void layer_norm_bwd_kernel(
     const uint4* __restrict__ s, const uint4* __restrict__ dn, const float* __restrict__ gamma,
@@ -98,17 +99,23 @@ __global__ __launch_bounds__(256) void layer_norm_bwd_kernel(
       }
     }
   }
-  float* pg = partial + (size_t)wave_id * 2 * M;
+  extern __shared__ float ln_bwd_smem[];              // [4 wavefronts][M], used twice
+  float* mine = ln_bwd_smem + (size_t)(threadIdx.x >> 6) * M;
+  float* pg = partial + (size_t)blockIdx.x * 2 * M;
 #pragma unroll
-  for (int j = 0; j < VPL; ++j)
+  for (int which = 0; which < 2; ++which) {           // 0: dgamma sums, 1: dbeta sums
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const int col = (lane + 64 * j) * K + i;
-      if (col < M) {
-        pg[col] = ag[j][i];
-        pg[M + col] = ab[j][i];
+    for (int j = 0; j < VPL; ++j)
+#pragma unroll
+      for (int i = 0; i < K; ++i) {
+        const int col = (lane + 64 * j) * K + i;
+        if (col < M) mine[col] = which == 0 ? ag[j][i] : ab[j][i];
       }
-    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < M; i += 256)
+      pg[which * M + i] = ((ln_bwd_smem[i] + ln_bwd_smem[M + i]) + ln_bwd_smem[2 * M + i]) + ln_bwd_smem[3 * M + i];
+    __syncthreads();
+  }
 }
 
 // dgamma[m] = sum_p partial[p][0][m], dbeta[m] = sum_p partial[p][1][m]: a block owns 16 of the
@@ -310,7 +317,7 @@ int launch_dense_wgrad(const moe_config& c, long long rows, int in, int out, con
 
 int layer_norm_bwd_parts(long long rows) {
   const long long blocks = (rows + 3) / 4;
-  return (int)(blocks < 256 ? blocks : 256) * 4;
+  return (int)(blocks < 1024 ? blocks : 1024);
 }
 
 int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const float* gamma,
@@ -319,12 +326,13 @@ int launch_layer_norm_bwd(int act_dtype, const void* s, const void* dn, const fl
   const int elt = act_dtype == MOE_F32 ? 4 : 2;
   const int vec_per_row = M * elt / 16;
   const int vpl = (vec_per_row + 63) / 64;
-  if (vpl > 8) return MOE_EUNSUPPORTED;
+  const size_t lds = (size_t)4 * M * sizeof(float);
+  if (vpl > 8 || lds > 64 * 1024) return MOE_EUNSUPPORTED;
   const int parts = layer_norm_bwd_parts(rows);
-  const unsigned grid = (unsigned)(parts / 4);
+  const unsigned grid = (unsigned)parts;
   const float eps = 1e-6f;
 #define MOE_LNB_CASE(T, V)                                                                    \
-  hipLaunchKernelGGL((layer_norm_bwd_kernel<T, V>), dim3(grid), dim3(256), 0, st,             \
+  hipLaunchKernelGGL((layer_norm_bwd_kernel<T, V>), dim3(grid), dim3(256), lds, st,           \
                      static_cast<const uint4*>(s), static_cast<const uint4*>(dn), gamma,      \
                      static_cast<const uint4*>(dres), static_cast<uint4*>(dx), partial, M,    \
                      vec_per_row, rows, eps)
