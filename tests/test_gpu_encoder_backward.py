@@ -195,3 +195,23 @@ def test_encoder_training_step_replays_from_a_hip_graph():
             assert torch.equal(grads["wqkv"][i], g_e["wqkv"][i]) and torch.equal(grads["wo_att"][i], g_e["wo_att"][i])
         for i in range(4):
             assert torch.equal(grads["ln_gamma"][i], g_e["ln_gamma"][i]) and torch.equal(grads["ln_beta"][i], g_e["ln_beta"][i])
+
+
+def test_encoder_backward_is_linear_in_the_upstream_gradient():
+    """Every backward kernel is linear in the incoming gradient and a factor of 4 is exact in
+    floating point, so scaling dy and daux by 4 must scale every result by exactly 4."""
+    cfg, B, L, heads, d = CASES[1]
+    dims = moe.EncoderDims(B, L, heads, d)
+    inp = make_inputs(cfg, device=DEV)
+    w = make_encoder_weights(cfg, heads, d, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    _, _, dx1, g1 = _gpu_backward(cfg, dims, inp, w, dy, daux)
+    _, _, dx4, g4 = _gpu_backward(cfg, dims, inp, w, dy * 4, daux * 4)
+    assert torch.equal(dx4, dx1 * 4)
+    for k in ("w1", "w2", "wg", "wi", "wo"):
+        assert torch.equal(g4[k], g1[k] * 4), k
+    for i in range(2):
+        assert torch.equal(g4["wqkv"][i], g1["wqkv"][i] * 4) and torch.equal(g4["wo_att"][i], g1["wo_att"][i] * 4)
+    for i in range(4):
+        assert torch.equal(g4["ln_gamma"][i], g1["ln_gamma"][i] * 4)
+        assert torch.equal(g4["ln_beta"][i], g1["ln_beta"][i] * 4)
