@@ -325,7 +325,11 @@ int moe_encoder_pair_forward_train(const moe_config* cfg, const moe_encoder_dims
 
 /* in: x, w as in the forward call; dy [B,L,M] (activation dtype), daux [G] fp32; fwd_ws as left by
  * moe_encoder_pair_forward_train.  out: dx [B,L,M]; every member of g (fully overwritten).
- * ws >= moe_encoder_backward_workspace_bytes, 256-byte aligned.  Errors as the other calls. */
+ * ws >= moe_encoder_backward_workspace_bytes, 256-byte aligned.  Errors as the other calls;
+ * MOE_EUNSUPPORTED also when the attention shape is served by neither form of the core's
+ * derivative: the MFMA kernels take bf16 with d in {64,128} and L % 128 == 0, the plain kernels
+ * need (2 L + 2 d) * 16 bytes of LDS <= 64 KB; and when M * 16 bytes > 64 KB (layer-norm
+ * parameter sums).  Results are bit-reproducible (no atomics). */
 int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dims, const void* x,
                               const moe_encoder_weights* w, const void* dy, const float* daux,
                               const void* fwd_ws, size_t fwd_ws_bytes, void* dx,
