@@ -57,6 +57,13 @@ __device__ __forceinline__ u32x4_t pack8(const float* v) {
   return u32x4_t{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
                  pack_bf16x2(v[6], v[7])};
 }
+// Consecutive workgroups go to different XCDs (8, each with its own L2).  This gives every XCD
+// a contiguous range of work items instead, so the blocks of one (sequence, head), which read
+// the same K / V (or Q / dO) rows, run under one L2.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned block, unsigned blocks) {
+  const unsigned per_xcd = blocks / 8;
+  return block < per_xcd * 8 ? (block % 8) * per_xcd + block / 8 : block;
+}
 __device__ __forceinline__ int swap_bits_2_3(int row) {
   return (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);
 }
@@ -87,8 +94,9 @@ __global__ __launch_bounds__(256, 1) void attention_bwd_dq_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hf = lane >> 5;
   const int qblocks = L / 128;
-  const int qb = blockIdx.x % qblocks;
-  const long long bh = blockIdx.x / qblocks;
+  const unsigned work = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int qb = work % qblocks;
+  const long long bh = work / qblocks;
   const int h = (int)(bh % heads);
   const long long b = bh / heads;
   const int A = heads * D;
@@ -209,8 +217,9 @@ __global__ __launch_bounds__(256, 1) void attention_bwd_dkv_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hf = lane >> 5;
   const int kblocks = L / 128;
-  const int kblk = blockIdx.x % kblocks;
-  const long long bh = blockIdx.x / kblocks;
+  const unsigned work = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int kblk = work % kblocks;
+  const long long bh = work / kblocks;
   const int h = (int)(bh % heads);
   const long long b = bh / heads;
   const int A = heads * D;

@@ -176,8 +176,14 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hf = lane >> 5;
   const int qblocks = L / 128;
-  const int qb = blockIdx.x % qblocks;
-  const long long bh = blockIdx.x / qblocks;
+  // Consecutive workgroups go to different XCDs (8, each with its own L2): give every XCD a
+  // contiguous range of work items, so the query blocks of one (sequence, head), which read
+  // the same K and V rows, run under one L2.
+  unsigned work = blockIdx.x;
+  const unsigned per_xcd = gridDim.x / 8;
+  if (work < per_xcd * 8) work = (work % 8) * per_xcd + work / 8;
+  const int qb = work % qblocks;
+  const long long bh = work / qblocks;
   const int h = (int)(bh % heads);
   const long long b = bh / heads;
   const int A = heads * D;
