@@ -122,3 +122,62 @@ def test_full_size_backward(name):
     # softmax gradients sum to zero over the experts of a token, hence so do the rows of dwg
     dwg = f64(got["dwg"])
     assert np.abs(dwg.sum(axis=1)).max() < 1e-4 * np.abs(dwg).sum(axis=1).max()
+
+
+@pytest.mark.timeout(900)
+def test_full_size_encoder_backward_on_sampled_sequences():
+    """Training forward + backward of the encoder pair at the benchmarked sizes (paper-shaped
+    MoE layer, 32 sequences of 1024 tokens, 16 heads of 128).  Everything before the MoE layer
+    is local to a sequence, so dx of a sampled sequence follows from the MoE oracle's input
+    gradient (computed for the whole batch) and that sequence's own chain: the oracle's chain
+    is evaluated at the GPU's forward activations of the sampled sequences."""
+    import time
+    import paper_2006_16668_amd as moe
+    from oracle import moe_oracle_backward as orb
+    from oracle import transformer_oracle_backward as trb
+    from test_gpu_encoder import _split_qkv, _staged
+    from test_gpu_encoder_backward import _gpu_backward
+    from workloads import make_encoder_weights, make_upstream
+    cfg = CONFIGS["paper"]
+    B, L, heads, d = 32, 1024, 16, 128
+    A = heads * d
+    dims = moe.EncoderDims(B, L, heads, d)
+    print(f"case {cfg} B={B} L={L} heads={heads} d={d}", flush=True)
+    inp = make_inputs(cfg, device=DEV)
+    w = make_encoder_weights(cfg, heads, d, device=DEV)
+    dy, daux = make_upstream(cfg, device=DEV)
+    _, _, dx, g = _gpu_backward(cfg, dims, inp, w, dy, daux)
+    assert torch.isfinite(dx.float()).all()
+    for k in ("w1", "w2", "wg"):
+        assert torch.isfinite(g[k].float()).all(), k
+    print("gpu backward done", flush=True)
+    r = _staged(cfg, dims, inp, w)
+    t0 = time.perf_counter()
+    m = orb.moe_backward(f64(r["n4"]), f64(inp.wg), f64(inp.u), ExpertWeightsF64(inp.wi),
+                         ExpertWeightsF64(inp.wo), cfg.C, f64(dy), f64(daux), experts=[])
+    print(f"MoE oracle backward done in {time.perf_counter() - t0:.0f} s", flush=True)
+    assert rel_fro(f64(g["wg"]), m["dwg"]) < 2e-2
+    gam = [f64(t) for t in w["ln_gamma"]]
+    flat = lambda t: t.reshape(B * L, cfg.M)
+    dn4 = m["dx"].reshape(B * L, cfg.M)
+    rng = np.random.default_rng(cfg.seed + 2)
+    for b in sorted(set(int(v) for v in rng.integers(0, B, 2))):
+        rows = slice(b * L, (b + 1) * L)
+        seq = lambda name: f64(flat(r[name])[rows]).reshape(1, L, cfg.M)
+        dln, _, _ = trb.layer_norm_backward(seq("c"), gam[3], dn4[rows].reshape(1, L, cfg.M))
+        gc = f64(flat(dy)[rows]).reshape(1, L, cfg.M) + dln
+        wq, wk, wv = _split_qkv(w["wqkv"][1], A)
+        dn3 = trb.self_attention_backward(seq("n3"), wq, wk, wv, f64(w["wo_att"][1]), heads, gc)[0]
+        gb = gc + trb.layer_norm_backward(seq("b"), gam[2], dn3)[0]
+        dn2 = trb.dense_ffn_backward(seq("n2"), f64(w["w1"]), f64(w["w2"]), gb)[0]
+        ga = gb + trb.layer_norm_backward(seq("a"), gam[1], dn2)[0]
+        wq, wk, wv = _split_qkv(w["wqkv"][0], A)
+        dn1 = trb.self_attention_backward(seq("n1"), wq, wk, wv, f64(w["wo_att"][0]), heads, ga)[0]
+        x_seq = f64(flat(inp.x)[rows]).reshape(1, L, cfg.M)
+        want = ga + trb.layer_norm_backward(x_seq, gam[0], dn1)[0]
+        got = f64(flat(dx)[rows]).reshape(1, L, cfg.M)
+        err = rel_fro(got, want)
+        print(f"sequence {b}: rel error of dx {err:.2e} ({time.perf_counter() - t0:.0f} s)", flush=True)
+        assert err < 1.5e-2, (b, err)
+        per_row = np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
+        assert per_row.max() < 0.12, per_row.max()
