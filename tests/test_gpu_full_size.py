@@ -126,7 +126,7 @@ def test_full_size_backward(name):
 
 @pytest.mark.timeout(900)
 def test_full_size_encoder_backward_on_sampled_sequences():
-    """Training forward + backward of the encoder pair at the benchmarked sizes (paper-shaped
+    """Forward stages and the training forward + backward of the encoder pair at the benchmarked sizes (paper-shaped
     MoE layer, 32 sequences of 1024 tokens, 16 heads of 128).  Everything before the MoE layer
     is local to a sequence, so dx of a sampled sequence follows from the MoE oracle's input
     gradient (computed for the whole batch) and that sequence's own chain: the oracle's chain
@@ -134,6 +134,7 @@ def test_full_size_encoder_backward_on_sampled_sequences():
     import time
     import paper_2006_16668_amd as moe
     from oracle import moe_oracle_backward as orb
+    from oracle import transformer_oracle as tro
     from oracle import transformer_oracle_backward as trb
     from test_gpu_encoder import _split_qkv, _staged
     from test_gpu_encoder_backward import _gpu_backward
@@ -164,6 +165,13 @@ def test_full_size_encoder_backward_on_sampled_sequences():
     for b in sorted(set(int(v) for v in rng.integers(0, B, 2))):
         rows = slice(b * L, (b + 1) * L)
         seq = lambda name: f64(flat(r[name])[rows]).reshape(1, L, cfg.M)
+        # the forward stages of this sequence, each on the GPU's own stage input
+        for i, (u_name, out_name) in enumerate((("n1", "att1"), ("n3", "att2"))):
+            wq, wk, wv = _split_qkv(w["wqkv"][i], A)
+            want_att = tro.self_attention(seq(u_name), wq, wk, wv, f64(w["wo_att"][i]), heads)
+            assert rel_fro(seq(out_name), want_att) < 2e-2, out_name
+        assert rel_fro(seq("ffn"), tro.dense_ffn(seq("n2"), f64(w["w1"]), f64(w["w2"]))) < 2e-2
+        assert rel_fro(seq("n4"), tro.layer_norm(seq("c"), gam[3], f64(w["ln_beta"][3]))) < 5e-3
         dln, _, _ = trb.layer_norm_backward(seq("c"), gam[3], dn4[rows].reshape(1, L, cfg.M))
         gc = f64(flat(dy)[rows]).reshape(1, L, cfg.M) + dln
         wq, wk, wv = _split_qkv(w["wqkv"][1], A)
