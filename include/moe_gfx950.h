@@ -95,6 +95,23 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
              float* gates_opt, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moe_gate for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (minus ws / ws_bytes), same kernels and bit-identical results; the scratch memory
+ * is an array of moe_gate_noalloc_max_bytes() = 16 MiB inside the library's own device image,
+ * one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ * Returns MOE_EWORKSPACE (nothing enqueued) when moe_gate_workspace_bytes(cfg) exceeds that
+ * size.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two
+ * streams, two host threads) race; calls on one stream are ordered and safe.  The first call
+ * on a device looks the array's address up (a host-side query, no allocation).
+ */
+int moe_gate_noalloc_max_bytes(size_t* bytes);
+int moe_gate_noalloc(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                     int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
+                     int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
+                     float* gates_opt, void* stream);
+
+/*
  * Dispatch (Algorithm 2, the GSEC,GSM->EGCM einsum, computed as the gather of
  * Section 3.2):  buf[e,g,c,:] = x[g, src_token[e,g,c], :], zeros where
  * src_token is -1.

@@ -21,7 +21,7 @@ MOE_F32, MOE_BF16 = 0, 1
 SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
-           "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
+           "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
            "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
            "moe_backward", "moe_backward_events", "moe_add_layer_norm",
            "moe_attention_workspace_bytes", "moe_encoder_workspace_bytes", "moe_self_attention",
@@ -108,6 +108,8 @@ def load_library() -> ctypes.CDLL:
         "moe_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_forward_fuses_dispatch": [cfgp, ctypes.POINTER(i32)],
         "moe_gate": [cfgp] + [vp] * 13 + [sz, vp],
+        "moe_gate_noalloc": [cfgp] + [vp] * 13,
+        "moe_gate_noalloc_max_bytes": [ctypes.POINTER(sz)],
         "moe_dispatch": [cfgp, vp, vp, vp, vp],
         "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
         "moe_combine": [cfgp, vp, vp, vp, vp, vp, vp],
@@ -213,6 +215,28 @@ def moe_gate(shape: MoEShape, x, wg, u, expert_idx, slot, weight, fill, src_toke
         _ptr(c1, i32, (G, E), "c1"), _ptr(mean_gate, f32, (G, E), "mean_gate"),
         _ptr(aux, f32, (G,), "aux"), _ptr(gates_opt, f32, (G, S, E), "gates_opt"),
         wsp, wsn, _stream()), "moe_gate")
+
+
+def moe_gate_noalloc_max_bytes() -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().moe_gate_noalloc_max_bytes(ctypes.byref(n)), "moe_gate_noalloc_max_bytes")
+    return n.value
+
+
+def moe_gate_noalloc(shape: MoEShape, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
+                     mean_gate, aux, gates_opt):
+    """moe_gate whose scratch is the library's own per-GPU array (no workspace argument)."""
+    G, S, M, E, C = shape.G, shape.S, shape.M, shape.E, shape.C
+    i32, f32 = torch.int32, torch.float32
+    c = shape._c()
+    _check(load_library().moe_gate_noalloc(
+        ctypes.byref(c), _ptr(x, shape.torch_dtype, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"),
+        _ptr(u, f32, (G, S), "u"), _ptr(expert_idx, i32, (G, S, 2), "expert_idx"),
+        _ptr(slot, i32, (G, S, 2), "slot"), _ptr(weight, f32, (G, S, 2), "weight"),
+        _ptr(fill, i32, (G, E), "fill"), _ptr(src_token, i32, (E, G, C), "src_token"),
+        _ptr(c1, i32, (G, E), "c1"), _ptr(mean_gate, f32, (G, E), "mean_gate"),
+        _ptr(aux, f32, (G,), "aux"), _ptr(gates_opt, f32, (G, S, E), "gates_opt"),
+        _stream()), "moe_gate_noalloc")
 
 
 def moe_dispatch(shape: MoEShape, x, src_token, buf):

@@ -1,11 +1,36 @@
 // C ABI of the library: argument checks, workspace carving, kernel sequencing.
 // Every step of the layer runs in the kernels of gate.hip, dispatch_combine.hip
 // and expert_gemm.hip; nothing here computes.
+#include <mutex>
 #include "common.h"
 
 namespace {
 
 using moe::align_up;
+
+// Scratch memory of moe_gate_noalloc: one array per GPU, owned by the library's code object
+// (it exists from the moment the library is loaded on a device until the process ends).
+constexpr size_t kGateScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kGateScratchBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// stand-in for the symbol; its address on a device comes from hipGetSymbolAddress, once per
+// device with that device current, and is kept.
+constexpr int kScratchDevices = 64;
+int gate_scratch_ptr(void** out) {
+  static std::mutex lock;
+  static void* ptr_of[kScratchDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return MOE_EHIP;
+  std::lock_guard<std::mutex> guard(lock);
+  if (ptr_of[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MOE_EHIP;
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return MOE_OK;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -332,6 +357,32 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
   if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
   if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
+  return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
+                          mean_gate, aux, gates_opt, ws, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int moe_gate_noalloc_max_bytes(size_t* bytes) {
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = kGateScratchBytes;
+  return MOE_OK;
+}
+
+int moe_gate_noalloc(const moe_config* cfg, const void* x, const float* wg, const float* u,
+                     int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
+                     int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
+                     float* gates_opt, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, wg, u, expert_idx, slot, weight, fill, src_token, c1, mean_gate, aux};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
+  if (moe::gate_workspace_bytes(*cfg) > kGateScratchBytes) return MOE_EWORKSPACE;
+  void* ws = nullptr;
+  const int rs = gate_scratch_ptr(&ws);
+  if (rs != MOE_OK) return rs;
+  // every word of the scratch that the kernels read is written earlier in the same call
+  // (chunk histograms, gate sums and the packed weights), so nothing has to be cleared
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
                           mean_gate, aux, gates_opt, ws, nullptr, static_cast<hipStream_t>(stream));
 }
