@@ -22,6 +22,7 @@ by eye:
 * ``dense_combine_weights``    -- Section 3.1: the [G,S,E,C] combine_weights tensor
                                    and the binary dispatch_mask
 * ``moe_forward_einsum``       -- Algorithm 2, the einsums as printed (tiny inputs)
+* ``expert_hidden``            -- Eq. 2, inner half:  ReLU(wi_e . x)
 * ``expert_ffn``               -- Eq. 2:  FFN_e(x) = wo_e . ReLU(wi_e . x)
 * ``moe_forward``              -- Eq. 1-3:  y_s = sum_e G_{s,e} FFN_e(x_s)
 * ``moe_forward_tokens``       -- Eq. 1-3 for a chosen subset of tokens
@@ -261,9 +262,14 @@ def moe_forward_einsum(x, wg, u, wi, wo, C, literal_pass2=False):
 # --------------------------------------------------------------------------
 # Eq. 1-3: the layer by its definition
 # --------------------------------------------------------------------------
+def expert_hidden(rows, wi_e):
+    """The inner half of Eq. 2 for a batch of rows: ReLU(rows . wi_e)   (no bias)."""
+    return np.maximum(_f64(rows) @ _f64(wi_e), 0.0)
+
+
 def expert_ffn(rows, wi_e, wo_e):
     """Eq. 2 for a batch of rows: relu(rows . wi_e) . wo_e   (no bias)."""
-    return np.maximum(_f64(rows) @ _f64(wi_e), 0.0) @ _f64(wo_e)
+    return expert_hidden(rows, wi_e) @ _f64(wo_e)
 
 
 def moe_forward(x, wg, u, wi, wo, C, literal_pass2=False):

@@ -31,6 +31,11 @@ def test_expert_ffn_against_explicit_loops():
             want[r, m] = sum(hid[h] * wo[h, m] for h in range(H))
     np.testing.assert_allclose(orc.expert_ffn(rows, wi, wo), want, rtol=1e-13, atol=1e-14)
     assert (orc.expert_ffn(np.zeros((2, M)), wi, wo) == 0).all()      # FFN_e(0) = 0
+    # the inner half on its own: index loops again, negative pre-activations clipped to 0
+    hid = np.array([[max(0.0, sum(rows[r, m] * wi[m, h] for m in range(M))) for h in range(H)]
+                    for r in range(R)])
+    np.testing.assert_allclose(orc.expert_hidden(rows, wi), hid, rtol=1e-13, atol=1e-14)
+    assert (hid == 0).any() and (hid > 0).any()
 
 
 def test_two_experts_is_the_dense_mixture():
