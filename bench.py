@@ -24,13 +24,37 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch of the expert GEMMs on the `paper` workload, from two
-# rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB -> bytes; the factors come
-# from a plain 1 GiB copy in the same runs).  Summary: profiles/moe_layer_paper_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {
-    "paper": {"expert_gemm1": (804372 * 2.0 + 1048576) * 1024,
-              "expert_gemm2": (789628 * 2.0 + 131072) * 1024},
-}
+STAGES = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
+
+
+def measured_traffic(cfg_name):
+    """HBM-side bytes per launch of each stage from the committed rocprofv3 --pmc summary of this
+    workload (profiles/moe_layer_<workload>_hbm_traffic.md: FETCH_SIZE and WRITE_SIZE in KiB per
+    dispatch, scaled by the factors a plain copy of known size gives in the same runs).  Returns
+    ({stage: bytes}, source) or ({}, None) when there is no summary; the source string names the
+    file and the date it states, so a figure can never outlive its profile unnoticed."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"moe_layer_{cfg_name}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return {}, None
+    text = open(path).read()
+    fs = re.search(r"FETCH_SIZE is scaled by ([0-9.]+), WRITE_SIZE by ([0-9.]+)", text)
+    date = re.search(r"Measured: (\S+)", text)
+    if not fs:
+        return {}, None
+    kf, kw = float(fs.group(1)), float(fs.group(2))
+    out = {}
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0].strip("`") in STAGES:
+            try:
+                fetch = float(cells[2].replace(" ", "").replace(",", ""))
+                write = float(cells[3].replace(" ", "").replace(",", ""))
+            except ValueError:
+                continue
+            out[cells[0].strip("`")] = (fetch * kf + write * kw) * 1024
+    src = f"profiles/{os.path.basename(path)}" + (f" (measured {date.group(1)})" if date else "")
+    return out, src
 
 
 def cpu_baseline(cfg, inp, seconds_hint=20.0):
@@ -307,6 +331,154 @@ def time_f32_layer(moe, cfg, K, W):
             "note": "same workload in fp32 (v_mfma_f32_32x32x2_f32); not part of value"}
 
 
+def gemm_rows(moe, cfg, sh, fill):
+    """Rows per GEMM launch: occupied slots (the algorithmic work), every slot of the buffer, and
+    the rows the launches really multiply (whole 256-row tiles of each expert's packed rows when
+    the layer packs them, else every slot)."""
+    import torch
+    kept = int(fill.sum().item())
+    padded = cfg.E * cfg.G * cfg.C
+    multiplied = padded
+    if moe.moe_forward_fuses_dispatch(sh) and hasattr(moe, "moe_forward_packs_rows") \
+            and moe.moe_forward_packs_rows(sh):
+        per_e = fill.sum(dim=0)
+        multiplied = int((((per_e + 255) // 256) * 256).sum().item())
+    return kept, padded, multiplied
+
+
+def measure_forward(moe, cfg, inp, K, W, power=False):
+    """K timed calls of moe_forward_events after W warm-up calls of moe_forward; stage times from
+    HIP events recorded inside the timed calls on the kernels' own stream."""
+    import torch
+    dev = inp.x.device
+    sh = moe.MoEShape(cfg.G, cfg.S, cfg.M, cfg.H, cfg.E, cfg.C, cfg.act_dtype)
+    y = torch.empty_like(inp.x)
+    aux = torch.empty(cfg.G, dtype=torch.float32, device=dev)
+    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    # occupied expert rows (algorithmic work of the GEMMs counts kept rows only)
+    i32 = dict(dtype=torch.int32, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    fill = torch.empty((cfg.G, cfg.E), **i32)
+    gws = torch.empty(moe.moe_gate_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    moe.moe_gate(sh, inp.x, inp.wg, inp.u, torch.empty((cfg.G, cfg.S, 2), **i32),
+                 torch.empty((cfg.G, cfg.S, 2), **i32), torch.empty((cfg.G, cfg.S, 2), **f32), fill,
+                 torch.empty((cfg.E, cfg.G, cfg.C), **i32), torch.empty((cfg.G, cfg.E), **i32),
+                 torch.empty((cfg.G, cfg.E), **f32), torch.empty((cfg.G,), **f32), None, gws)
+    torch.cuda.synchronize()
+    kept_rows, padded_rows, multiplied_rows = gemm_rows(moe, cfg, sh, fill)
+    del gws
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
+              for _ in range(K)]
+    for evs in events:                      # create the handles
+        for e in evs:
+            e.record()
+    for _ in range(W):
+        moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        moe.moe_forward_events(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws, events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    pw = None
+    if power:
+        # power / clock state under this load: a separate, longer, untimed run of the same calls
+        with PowerSampler() as ps:
+            for _ in range(max(K, int(1500.0 / max((t1 - t0) * 1e3 / K, 0.05)))):      # about 1.5 s
+                moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
+            torch.cuda.synchronize()
+        pw = ps.summary()
+    per_call = {n: sorted(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K))
+                for i, n in enumerate(STAGES)}
+    return {"sh": sh, "ws": ws, "y": y, "aux": aux, "wall_s": t1 - t0, "power": pw,
+            "kept_rows": kept_rows, "padded_rows": padded_rows, "multiplied_rows": multiplied_rows,
+            "stage_ms": {n: sum(v) / K for n, v in per_call.items()},
+            "stage_median": {n: v[K // 2] for n, v in per_call.items()},
+            "stage_min": {n: v[0] for n, v in per_call.items()}}
+
+
+def stage_rooflines(moe, cfg, m):
+    """Per stage: algorithmic flops and bytes of one launch, which roofline binds it (the larger of
+    flops / MFMA peak and bytes / HBM peak) and the achieved fraction of each."""
+    elt = 2 if cfg.act_dtype == "bf16" else 4
+    peak = PEAK_BF16_TFLOPS if cfg.act_dtype == "bf16" else PEAK_F32_TFLOPS
+    kept, N, row_b = m["kept_rows"], cfg.N, cfg.M * elt
+    w_bytes = cfg.E * cfg.M * cfg.H * elt
+    work = {  # stage: (flops, bytes) of one launch; GEMM work counts the occupied rows only
+        # the gate's logits run as three bf16 MFMA passes (wg in three exact bf16 terms)
+        "gate": (2.0 * (3 if cfg.act_dtype == "bf16" else 1) * N * cfg.M * cfg.E,
+                 N * row_b + cfg.M * cfg.E * 4 + N * 28),
+        "dispatch": (0.0, (kept + m["padded_rows"]) * row_b),     # read kept rows, write every slot
+        "expert_gemm1": (2.0 * cfg.M * cfg.H * kept, w_bytes + kept * row_b + kept * cfg.H * elt),
+        "expert_gemm2": (2.0 * cfg.M * cfg.H * kept, w_bytes + kept * cfg.H * elt + kept * row_b),
+        "combine": (0.0, (kept + N) * row_b),
+    }
+    if moe.moe_forward_fuses_dispatch(m["sh"]):
+        del work["dispatch"]                 # no dispatch kernel ran: the stage is an empty gap
+    out = {}
+    for n, (fl, by) in work.items():
+        t = m["stage_ms"][n] * 1e-3
+        t_mfma, t_hbm = fl / (peak * 1e12), by / (PEAK_HBM_GBS * 1e9)
+        out[n] = {"ms": m["stage_ms"][n], "bound": "mfma" if t_mfma > t_hbm else "hbm",
+                  "mfma_frac": fl / t / 1e12 / peak, "hbm_frac": by / t / 1e9 / PEAK_HBM_GBS,
+                  "frac_of_bound": max(t_mfma, t_hbm) / t,
+                  "algorithmic_GB": by / 1e9, "algorithmic_TFLOP": fl / 1e12}
+    return out
+
+
+def headline_roofline(moe, cfg, m, roofs):
+    """The `roofline` object of the JSON line: the slower of the two expert GEMM launches, against
+    the roofline that bounds it (bf16 MFMA unless the weights' HBM traffic takes longer)."""
+    peak = PEAK_BF16_TFLOPS if cfg.act_dtype == "bf16" else PEAK_F32_TFLOPS
+    dom = max(("expert_gemm1", "expert_gemm2"), key=lambda n: m["stage_ms"][n])
+    r = roofs[dom]
+    traffic, source = measured_traffic(cfg.name)
+    kern = ("expert_gemm_bf16_dma_kernel" if cfg.act_dtype == "bf16" else "gemm_f32_mfma_kernel") + f" ({dom})"
+    t = m["stage_ms"][dom] * 1e-3
+    if r["bound"] == "mfma":
+        out = {"bound": "mfma", "kernel": kern, "achieved": r["mfma_frac"] * peak, "peak": peak,
+               "unit": "TFLOP/s", "frac": r["mfma_frac"]}
+    else:
+        out = {"bound": "hbm", "kernel": kern, "achieved": r["hbm_frac"] * PEAK_HBM_GBS,
+               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["hbm_frac"],
+               "mfma_frac": r["mfma_frac"]}
+    out["traffic"] = traffic.get(dom)
+    out["traffic_source"] = source
+    out["achieved_padded_rows_TFLOPs"] = 2.0 * cfg.M * cfg.H * m["padded_rows"] / t / 1e12
+    out["achieved_multiplied_rows_TFLOPs"] = 2.0 * cfg.M * cfg.H * m["multiplied_rows"] / t / 1e12
+    return out
+
+
+def workload_name(cfg):
+    return (f"{cfg.name}: G={cfg.G} S={cfg.S} M={cfg.M} H={cfg.H} E={cfg.E} C={cfg.C}, top-2, "
+            f"{cfg.act_dtype} experts, fp32 gate")
+
+
+def other_config(moe, name, K, W):
+    """One more workload of the target list (forward only), measured like the headline one."""
+    import torch
+    from workloads import CONFIGS, make_inputs
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg, device="cuda:0")
+    m = measure_forward(moe, cfg, inp, K, W)
+    roofs = stage_rooflines(moe, cfg, m)
+    peak = PEAK_BF16_TFLOPS if cfg.act_dtype == "bf16" else PEAK_F32_TFLOPS
+    gemm_s = (m["stage_ms"]["expert_gemm1"] + m["stage_ms"]["expert_gemm2"]) * 1e-3
+    out = {"workload": workload_name(cfg), "tokens": cfg.N, "steps": K, "warmup": W,
+           "tokens_per_s": cfg.N * K / m["wall_s"], "ms_per_step": m["wall_s"] * 1e3 / K,
+           "kept_rows": m["kept_rows"], "padded_rows": m["padded_rows"],
+           "multiplied_rows": m["multiplied_rows"],
+           "stages_ms": m["stage_ms"], "stages_ms_min": m["stage_min"],
+           "ffn_mfma_frac": 4.0 * cfg.M * cfg.H * m["kept_rows"] / gemm_s / 1e12 / peak,
+           "ffn_hbm_frac": (roofs["expert_gemm1"]["algorithmic_GB"] + roofs["expert_gemm2"]["algorithmic_GB"])
+                           / gemm_s / PEAK_HBM_GBS,
+           "stages": roofs, "roofline": headline_roofline(moe, cfg, m, roofs)}
+    del inp, m
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -325,6 +497,11 @@ def main():
                     help="skip the extra measurement of the same workload in fp32")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the extra (untimed for the metric) measurement of the backward pass")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the forward measurement of the other paper-shaped workloads "
+                         "(skewed, many_experts) that the default run appends")
+    ap.add_argument("--only-forward", action="store_true",
+                    help="the timed forward of --config and nothing else (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (yardstick for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters); not part of the timed region")
@@ -332,6 +509,9 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the layer on ONE GPU (one device's share of tokens); "
                  "the cross-device exchange is out of scope, so --gpus must be 1")
+    if args.only_forward:
+        args.no_cpu_baseline = args.no_encoder = args.no_yardsticks = args.no_f32 = True
+        args.no_backward = args.no_other_configs = True
 
     import torch
     import paper_2006_16668_amd as moe
@@ -341,23 +521,6 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     inp = make_inputs(cfg, device=dev)
-    sh = moe.MoEShape(cfg.G, cfg.S, cfg.M, cfg.H, cfg.E, cfg.C, cfg.act_dtype)
-    y = torch.empty_like(inp.x)
-    aux = torch.empty(cfg.G, dtype=torch.float32, device=dev)
-    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
-
-    # occupied expert rows (algorithmic work of the GEMMs counts kept rows only)
-    i32 = dict(dtype=torch.int32, device=dev)
-    f32 = dict(dtype=torch.float32, device=dev)
-    fill = torch.empty((cfg.G, cfg.E), **i32)
-    gws = torch.empty(moe.moe_gate_workspace_bytes(sh), dtype=torch.uint8, device=dev)
-    moe.moe_gate(sh, inp.x, inp.wg, inp.u, torch.empty((cfg.G, cfg.S, 2), **i32),
-                 torch.empty((cfg.G, cfg.S, 2), **i32), torch.empty((cfg.G, cfg.S, 2), **f32), fill,
-                 torch.empty((cfg.E, cfg.G, cfg.C), **i32), torch.empty((cfg.G, cfg.E), **i32),
-                 torch.empty((cfg.G, cfg.E), **f32), torch.empty((cfg.G,), **f32), None, gws)
-    torch.cuda.synchronize()
-    kept_rows = int(fill.sum().item())
-    padded_rows = cfg.E * cfg.G * cfg.C
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -367,72 +530,30 @@ def main():
         del src, dst
 
     K, W = args.steps, args.warmup
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
-              for _ in range(K)]
-    for evs in events:                      # create the handles
-        for e in evs:
-            e.record()
-    for _ in range(W):
-        moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(K):
-        moe.moe_forward_events(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws, events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    # power / clock state under this load: a separate, longer, untimed run of the same calls
-    with PowerSampler() as ps:
-        for _ in range(max(K, int(1500.0 / max((t1 - t0) * 1e3 / K, 0.05)))):      # about 1.5 s
-            moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
-        torch.cuda.synchronize()
-    power = ps.summary()
-
-    ms_per_step = (t1 - t0) * 1e3 / K
-    names = ["gate", "dispatch", "expert_gemm1", "expert_gemm2", "combine"]
-    per_call = {n: sorted(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K))
-                for i, n in enumerate(names)}
-    stage_ms = {n: sum(v) / K for n, v in per_call.items()}
-    stage_median = {n: v[K // 2] for n, v in per_call.items()}
-    stage_min = {n: v[0] for n, v in per_call.items()}
-    elt = 2 if cfg.act_dtype == "bf16" else 4
-    flops_launch = 2.0 * cfg.M * cfg.H * kept_rows            # per GEMM launch, kept rows only
-    dom = max(("expert_gemm1", "expert_gemm2"), key=lambda n: stage_ms[n])
-    achieved = flops_launch / (stage_ms[dom] * 1e-3) / 1e12
+    m = measure_forward(moe, cfg, inp, K, W, power=not args.only_forward)
+    sh, ws, y, aux = m["sh"], m["ws"], m["y"], m["aux"]
+    kept_rows, padded_rows = m["kept_rows"], m["padded_rows"]
+    stage_ms = dict(m["stage_ms"])
+    roofs = stage_rooflines(moe, cfg, m)
     peak = PEAK_BF16_TFLOPS if cfg.act_dtype == "bf16" else PEAK_F32_TFLOPS
-    row_b = cfg.M * elt
-    hbm_bytes = {  # algorithmic bytes per launch of the memory-bound stages
-        "gate": cfg.N * row_b + cfg.M * cfg.E * 4 + cfg.N * 28,
-        "dispatch": (kept_rows + padded_rows) * row_b,        # read kept rows, write every slot
-        "combine": (kept_rows + cfg.N) * row_b,
-    }
+    flops_launch = 2.0 * cfg.M * cfg.H * kept_rows            # per GEMM launch, kept rows only
     if moe.moe_forward_fuses_dispatch(sh):
-        # no dispatch kernel ran: its stage is the gap between two event records
-        del hbm_bytes["dispatch"]
         stage_ms["dispatch_fused_into_gemm1"] = True
     out = {
-        "metric": "MoE-layer forward tokens/sec on 1 MI355X", "value": cfg.N * K / (t1 - t0),
-        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "metric": "MoE-layer forward tokens/sec on 1 MI355X", "value": cfg.N * K / m["wall_s"],
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": m["wall_s"] * 1e3 / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.act_dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: G={cfg.G} S={cfg.S} M={cfg.M} H={cfg.H} E={cfg.E} "
-                               f"C={cfg.C}, top-2, {cfg.act_dtype} experts, fp32 gate",
-                   "tokens": cfg.N, "kept_rows": kept_rows, "padded_rows": padded_rows},
-        "roofline": {"bound": "mfma", "kernel": ("expert_gemm_bf16_dma_kernel" if cfg.act_dtype == "bf16"
-                                                   else "gemm_f32_mfma_kernel") + f" ({dom})",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
-                     "achieved_padded_rows": 2.0 * cfg.M * cfg.H * padded_rows / (stage_ms[dom] * 1e-3) / 1e12},
-        "power_state": power,
-        "stages_ms": stage_ms, "stages_ms_median": stage_median, "stages_ms_min": stage_min,
-        # the gate's logits run as three bf16 MFMA passes (wg in three bf16 terms): at E > 64 that,
-        # not HBM, bounds the stage
-        "gate_mfma_frac": (2.0 * 3 * cfg.N * cfg.M * cfg.E / (stage_ms["gate"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
-                           if cfg.act_dtype == "bf16" else None),
-        "stages_hbm_frac": {n: hbm_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS
-                            for n in hbm_bytes},
+        "config": {"workload": workload_name(cfg), "tokens": cfg.N, "kept_rows": kept_rows,
+                   "padded_rows": padded_rows, "multiplied_rows": m["multiplied_rows"]},
+        "roofline": headline_roofline(moe, cfg, m, roofs),
+        "power_state": m["power"],
+        "stages_ms": stage_ms, "stages_ms_median": m["stage_median"], "stages_ms_min": m["stage_min"],
+        "gate_mfma_frac": roofs["gate"]["mfma_frac"] if cfg.act_dtype == "bf16" else None,
+        "stages_hbm_frac": {n: roofs[n]["hbm_frac"] for n in ("gate", "dispatch", "combine") if n in roofs},
         "ffn_mfma_frac": 2 * flops_launch / ((stage_ms["expert_gemm1"] + stage_ms["expert_gemm2"]) * 1e-3)
                          / 1e12 / peak,
+        "stages": roofs,
     }
     if args.hip_graph:
         graph = torch.cuda.CUDAGraph()
@@ -452,12 +573,18 @@ def main():
         out["yardsticks"] = yardsticks(cfg, dev)
     if not args.no_backward:
         out["backward"] = time_backward(moe, cfg, sh, inp, ws, y, aux, K, W, kept_rows, peak)
+    del ws, y, m
+    torch.cuda.empty_cache()
     if not args.no_f32 and cfg.act_dtype == "bf16":
-        del ws, y
-        torch.cuda.empty_cache()
         out["f32_layer"] = time_f32_layer(moe, cfg, min(K, 5), min(W, 2))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp)
+    if not args.no_other_configs:
+        # the other workloads the throughput target is stated for; `value` stays the headline one
+        del inp
+        torch.cuda.empty_cache()
+        out["other_configs"] = {n: other_config(moe, n, K, W)
+                                for n in ("paper", "skewed", "many_experts") if n != cfg.name}
     print(json.dumps(out))
 
 
