@@ -124,17 +124,27 @@ int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token,
  * Expert networks (Eq. 2; Algorithm 2, EGCM,EMH->EGCH, relu, EGCH,EHM->EGCM):
  *   h[e]   = relu( buf[e] . wi[e] )        [G*C, M] x [M, H]
  *   out[e] = h[e] . wo[e]                  [G*C, H] x [H, M]
- * Rows of buf are processed whether occupied or not (an empty row is zero and
- * FFN_e(0) = 0 since the experts have no bias).  The output keeps the EGCM
- * order on one device (the paper prints GECM, its layout after the reverse
- * exchange between devices).
+ * The output keeps the EGCM order on one device (the paper prints GECM, its layout after the
+ * reverse exchange between devices).
  * in : buf [E,G,C,M];  wi [E,M,H];  wo [E,H,M]   (act_dtype)
- * tmp: h_ws [E,G,C,H] act_dtype (caller-provided scratch)
+ *      fill [G,E] i32 or NULL: occupied slots per (group, expert) as moe_gate returns them; the
+ *      occupied slots of a segment buf[e,g,:,:] are its first fill[g,e] ones
+ * tmp: h_ws [E,G,C,H] act_dtype (caller-provided scratch, contents private to the call)
+ *      ws  NULL, or moe_expert_ffn_workspace_bytes(cfg) bytes, 256-byte aligned
  * out: out [E,G,C,M] act_dtype
+ * Without fill (or without ws) every row of buf is multiplied, occupied or not: an empty row is
+ * zero and FFN_e(0) = 0 since the experts have no bias (Section 2.2, "Expert capacity": a
+ * buffer position holds a token or nothing).  With fill and ws, and when
+ * moe_forward_packs_rows(cfg) says the kernels take the shape, only the occupied slots are
+ * multiplied: the kernels pack each expert's occupied rows to the front of its block (row maps
+ * in ws), multiply whole 256-row tiles of them and store each result row at its slot of out;
+ * the slots c >= fill[g,e] of out are then NOT written (combine never reads them).  Occupied
+ * rows get bit-identical results either way.
  * bf16 requires M % 8 == 0 and H % 8 == 0 (16-byte rows), else MOE_EUNSUPPORTED.
  */
-int moe_expert_ffn(const moe_config* cfg, const void* buf, const void* wi, const void* wo,
-                   void* h_ws, void* out, void* stream);
+int moe_expert_ffn_workspace_bytes(const moe_config* cfg, size_t* bytes);
+int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, const void* wi,
+                   const void* wo, void* h_ws, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Combine (Eq. 3; Algorithm 2, the GSEC,EGCM->GSM einsum, computed as a gather):
@@ -165,6 +175,16 @@ int moe_forward(const moe_config* cfg, const void* x, const float* wg, const flo
  * Pure host function: *fused = 1 or 0; returns MOE_OK or the config's error.
  */
 int moe_forward_fuses_dispatch(const moe_config* cfg, int* fused);
+
+/*
+ * Whether moe_forward (and moe_expert_ffn with fill and ws) multiplies only the occupied
+ * expert rows for this config (Section 2.2, "Expert capacity"): the kept rows of an expert
+ * are packed to the front of its block of G*C rows and only the ceil(kept / 256) row tiles
+ * that hold them go through the two GEMMs.  It does so for bf16 layers with G*C, M and H
+ * all multiples of 256.  moe_forward_train keeps every slot in place.
+ * Pure host function: *packed = 1 or 0; returns MOE_OK or the config's error.
+ */
+int moe_forward_packs_rows(const moe_config* cfg, int* packed);
 
 /*
  * moe_forward with stage timing marks, for callers that measure the kernels of

@@ -21,7 +21,8 @@ MOE_F32, MOE_BF16 = 0, 1
 SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
-           "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
+           "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_dispatch",
+           "moe_expert_ffn_workspace_bytes", "moe_forward_packs_rows", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
            "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
            "moe_backward", "moe_backward_events", "moe_add_layer_norm",
            "moe_attention_workspace_bytes", "moe_encoder_workspace_bytes", "moe_self_attention",
@@ -111,7 +112,9 @@ def load_library() -> ctypes.CDLL:
         "moe_gate_noalloc": [cfgp] + [vp] * 13,
         "moe_gate_noalloc_max_bytes": [ctypes.POINTER(sz)],
         "moe_dispatch": [cfgp, vp, vp, vp, vp],
-        "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp],
+        "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "moe_expert_ffn_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_forward_packs_rows": [cfgp, ctypes.POINTER(i32)],
         "moe_combine": [cfgp, vp, vp, vp, vp, vp, vp],
         "moe_forward": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "moe_forward_events": [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
@@ -248,14 +251,34 @@ def moe_dispatch(shape: MoEShape, x, src_token, buf):
         _ptr(buf, shape.torch_dtype, (E, G, C, M), "buf"), _stream()), "moe_dispatch")
 
 
-def moe_expert_ffn(shape: MoEShape, buf, wi, wo, h_ws, out):
+def moe_forward_packs_rows(shape: MoEShape) -> bool:
+    n = ctypes.c_int(0)
+    c = shape._c()
+    _check(load_library().moe_forward_packs_rows(ctypes.byref(c), ctypes.byref(n)),
+           "moe_forward_packs_rows")
+    return bool(n.value)
+
+
+def moe_expert_ffn_workspace_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_expert_ffn_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
+           "moe_expert_ffn_workspace_bytes")
+    return n.value
+
+
+def moe_expert_ffn(shape: MoEShape, buf, wi, wo, h_ws, out, fill=None, ws=None):
+    """Positional arguments in the order they had before ``fill`` and ``ws`` existed; the C call
+    takes (cfg, buf, fill, wi, wo, h_ws, out, ws, ws_bytes, stream)."""
     G, M, H, E, C = shape.G, shape.M, shape.H, shape.E, shape.C
     dt = shape.torch_dtype
     c = shape._c()
+    wsp, wsn = _ws(ws) if ws is not None else (None, ctypes.c_size_t(0))
     _check(load_library().moe_expert_ffn(
-        ctypes.byref(c), _ptr(buf, dt, (E, G, C, M), "buf"), _ptr(wi, dt, (E, M, H), "wi"),
+        ctypes.byref(c), _ptr(buf, dt, (E, G, C, M), "buf"), _ptr(fill, torch.int32, (G, E), "fill"),
+        _ptr(wi, dt, (E, M, H), "wi"),
         _ptr(wo, dt, (E, H, M), "wo"), _ptr(h_ws, dt, (E, G, C, H), "h_ws"),
-        _ptr(out, dt, (E, G, C, M), "out"), _stream()), "moe_expert_ffn")
+        _ptr(out, dt, (E, G, C, M), "out"), wsp, wsn, _stream()), "moe_expert_ffn")
 
 
 def moe_combine(shape: MoEShape, out, expert_idx, slot, weight, y):

@@ -47,8 +47,8 @@ int check_config(const moe_config* c) {
 
 // Layout of the moe_forward workspace.
 struct ForwardWs {
-  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, gates, signbits, buf,
-      h, out, gate_ws, total;
+  size_t expert_idx, slot, weight, fill, src_token, c1, mean_gate, zero_row, packing, gates,
+      signbits, buf, h, out, gate_ws, total;
 };
 
 ForwardWs carve(const moe_config& c) {
@@ -65,6 +65,7 @@ ForwardWs carve(const moe_config& c) {
   w.c1 = take(GE * 4);
   w.mean_gate = take(GE * 4);
   w.zero_row = take((size_t)c.M * elt);
+  w.packing = take(moe::expert_ffn_can_pack(c) ? moe::row_packing_bytes(c) : 0);
   w.gates = take(N * c.E * 4);
   w.signbits = take(moe::expert_gemm1_can_gather(c) ? moe::expert_signbits_bytes(c) : 0);
   w.buf = take(rows * c.M * elt);
@@ -128,28 +129,40 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   // bf16 layers whose shape the persistent GEMM takes skip the dispatched buffer: the first
   // GEMM gathers its rows from x (then the dispatch mark coincides with the gate mark)
   const bool gather = moe::expert_gemm1_can_gather(*cfg);
+  // ... and, in the inference form, multiply only the occupied rows of each expert, packed to
+  // the front of its block (the training form keeps every slot in place for the backward pass)
+  const bool packed = !keep_gates && moe::expert_ffn_can_pack(*cfg);
+  const moe::RowPacking pk = moe::carve_row_packing(*cfg, base + w.packing);
   if (!mark(0)) return MOE_EHIP;
   rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
                         reinterpret_cast<int32_t*>(base + w.fill), src_token,
                         reinterpret_cast<int32_t*>(base + w.c1),
                         reinterpret_cast<float*>(base + w.mean_gate), aux,
                         keep_gates ? reinterpret_cast<float*>(base + w.gates) : nullptr,
-                        base + w.gate_ws, gather ? base + w.zero_row : nullptr, st);
+                        base + w.gate_ws, gather ? base + w.zero_row : nullptr,
+                        packed ? &pk : nullptr, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
   if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
-  rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
-                                                base + w.h, keep_gates ? base + w.signbits : nullptr,
-                                                st)
-              : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
-  if (rc != MOE_OK) return rc;
-  if (!mark(3)) return MOE_EHIP;
-  rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);
-  if (rc != MOE_OK) return rc;
+  if (packed) {
+    rc = moe::launch_expert_ffn_packed(*cfg, x, pk, base + w.zero_row, wi, wo, base + w.h,
+                                       base + w.out, false, st, events != nullptr ? events[3] : nullptr);
+    if (rc != MOE_OK) return rc;
+  } else {
+    rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
+                                                  base + w.h, keep_gates ? base + w.signbits : nullptr,
+                                                  st)
+                : moe::launch_expert_gemm1(*cfg, base + w.buf, wi, base + w.h, st);
+    if (rc != MOE_OK) return rc;
+    if (!mark(3)) return MOE_EHIP;
+    rc = moe::launch_expert_gemm2(*cfg, base + w.h, wo, base + w.out, st);
+    if (rc != MOE_OK) return rc;
+  }
   if (!mark(4)) return MOE_EHIP;
-  rc = moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight, y, st);
+  rc = moe::launch_combine(*cfg, base + w.out, expert_idx, slot, weight,
+                           packed ? pk.row_base : nullptr, y, st);
   if (rc != MOE_OK) return rc;
   return mark(5) ? MOE_OK : MOE_EHIP;
 }
@@ -358,7 +371,8 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
   if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
   if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
-                          mean_gate, aux, gates_opt, ws, nullptr, static_cast<hipStream_t>(stream));
+                          mean_gate, aux, gates_opt, ws, nullptr, nullptr,
+                          static_cast<hipStream_t>(stream));
 }
 
 int moe_gate_noalloc_max_bytes(size_t* bytes) {
@@ -384,7 +398,8 @@ int moe_gate_noalloc(const moe_config* cfg, const void* x, const float* wg, cons
   // every word of the scratch that the kernels read is written earlier in the same call
   // (chunk histograms, gate sums and the packed weights), so nothing has to be cleared
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
-                          mean_gate, aux, gates_opt, ws, nullptr, static_cast<hipStream_t>(stream));
+                          mean_gate, aux, gates_opt, ws, nullptr, nullptr,
+                          static_cast<hipStream_t>(stream));
 }
 
 int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token, void* buf,
@@ -397,14 +412,45 @@ int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token,
   return moe::launch_dispatch(*cfg, x, src_token, buf, static_cast<hipStream_t>(stream));
 }
 
-int moe_expert_ffn(const moe_config* cfg, const void* buf, const void* wi, const void* wo,
-                   void* h_ws, void* out, void* stream) {
+int moe_forward_packs_rows(const moe_config* cfg, int* packed) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (packed == nullptr) return MOE_EINVAL;
+  *packed = moe::expert_ffn_can_pack(*cfg) ? 1 : 0;
+  return MOE_OK;
+}
+
+int moe_expert_ffn_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  const size_t elt = cfg->act_dtype == MOE_F32 ? 4 : 2;
+  *bytes = moe::expert_ffn_can_pack(*cfg)
+               ? moe::row_packing_bytes(*cfg) + align_up((size_t)cfg->M * elt, 256) : 0;
+  return MOE_OK;
+}
+
+int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, const void* wi,
+                   const void* wo, void* h_ws, void* out, void* ws, size_t ws_bytes, void* stream) {
   const int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
   const void* req[] = {buf, wi, wo, h_ws, out};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if (fill != nullptr && !aligned16(fill)) return MOE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (fill != nullptr && ws != nullptr && moe::expert_ffn_can_pack(*cfg)) {
+    // occupied rows only: row maps from fill, the first GEMM gathers the occupied rows of buf,
+    // the second sends its rows back to their slots of out
+    if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_EINVAL;
+    const size_t maps = moe::row_packing_bytes(*cfg);
+    if (ws_bytes < maps + align_up((size_t)cfg->M * 2, 256)) return MOE_EWORKSPACE;
+    const moe::RowPacking pk = moe::carve_row_packing(*cfg, ws);
+    void* zero_row = static_cast<char*>(ws) + maps;
+    int r = moe::launch_row_maps_from_fill(*cfg, fill, pk, zero_row, st);
+    if (r != MOE_OK) return r;
+    return moe::launch_expert_ffn_packed(*cfg, buf, pk, zero_row, wi, wo, h_ws, out, true, st, nullptr);
+  }
   const int rc1 = moe::launch_expert_gemm1(*cfg, buf, wi, h_ws, st);
   if (rc1 != MOE_OK) return rc1;
   return moe::launch_expert_gemm2(*cfg, h_ws, wo, out, st);
@@ -417,7 +463,7 @@ int moe_combine(const moe_config* cfg, const void* out, const int32_t* expert_id
   const void* req[] = {out, expert_idx, slot, weight, y};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
-  return moe::launch_combine(*cfg, out, expert_idx, slot, weight, y,
+  return moe::launch_combine(*cfg, out, expert_idx, slot, weight, nullptr, y,
                              static_cast<hipStream_t>(stream));
 }
 

@@ -6,6 +6,8 @@
 
 namespace moe {
 
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
 constexpr int kWave = 64;
 constexpr int kChunk = 64;  // tokens per routing chunk (one wavefront)
 
@@ -85,19 +87,53 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// Packed row layout of the expert GEMMs (Section 2.2, "Expert capacity": a buffer position holds
+// a token or nothing, and FFN_e(0) = 0, so positions that hold nothing need not be multiplied).
+// The kept rows of expert e, in (group, slot) order, occupy rows 0 .. kept_e - 1 of its block of
+// R = G*C rows; only the ceil(kept_e / 256) row tiles that hold them are multiplied.
+struct RowPacking {
+  int32_t* row_base;     // [G,E]  kept rows of expert e in the groups before g
+  int32_t* packed_src;   // [E,R]  source row of packed row p (a row index into the A operand's
+                         //        matrix), -1 from kept_e to the end of the last occupied tile;
+                         //        rows of unoccupied tiles are not written
+  int32_t* row_tile_start;  // [E+1] occupied 256-row tiles of the experts before e; [E] = total
+};
+inline size_t row_packing_bytes(const moe_config& c) {      // the three arrays, each 256-aligned
+  const size_t rows = (size_t)c.E * c.G * c.C;
+  return align_up((size_t)c.G * c.E * 4, 256) + align_up(rows * 4, 256) +
+         align_up(((size_t)c.E + 1) * 4, 256);
+}
+inline RowPacking carve_row_packing(const moe_config& c, void* base) {
+  const size_t rows = (size_t)c.E * c.G * c.C;
+  char* p = static_cast<char*>(base);
+  RowPacking pk;
+  pk.row_base = reinterpret_cast<int32_t*>(p);
+  p += align_up((size_t)c.G * c.E * 4, 256);
+  pk.packed_src = reinterpret_cast<int32_t*>(p);
+  p += align_up(rows * 4, 256);
+  pk.row_tile_start = reinterpret_cast<int32_t*>(p);
+  return pk;
+}
 
 // host-side launchers (each returns a moe_status)
 // zero_row: NULL, or M bf16 elements that the gate also clears (see launch_expert_gemm1_gather)
+// packing: NULL, or the arrays of the packed row layout that the gate also fills (packed_src
+// then holds token rows g*S + s of x)
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
-                float* gates_opt, void* ws, void* zero_row, hipStream_t st);
+                float* gates_opt, void* ws, void* zero_row, const RowPacking* packing,
+                hipStream_t st);
+// the packed row layout from fill alone, sources = rows of an [E,G,C,M] buffer; clears zero_row
+int launch_row_maps_from_fill(const moe_config& c, const int32_t* fill, const RowPacking& pk,
+                              void* zero_row, hipStream_t st);
 size_t gate_workspace_bytes(const moe_config& c);
 int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token, void* buf,
                     hipStream_t st);
+// row_base: NULL (out is [E,G,C,M]) or the [G,E] offsets of the packed row layout
 int launch_combine(const moe_config& c, const void* out, const int32_t* expert_idx,
-                   const int32_t* slot, const float* weight, void* y, hipStream_t st);
+                   const int32_t* slot, const float* weight, const int32_t* row_base, void* y,
+                   hipStream_t st);
 // h = relu(buf . wi) and out = h . wo, one grouped GEMM launch each
 int launch_expert_gemm1(const moe_config& c, const void* buf, const void* wi, void* h,
                         hipStream_t st);
@@ -111,6 +147,11 @@ bool expert_gemm1_can_gather(const moe_config& c);
 int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t* src_token,
                                const void* zero_row, const void* wi, void* h, void* signbits,
                                hipStream_t st);
+// both GEMMs over the packed row layout (bf16 layers the persistent kernel takes, M >= 128)
+bool expert_ffn_can_pack(const moe_config& c);
+int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
+                             const void* zero_row, const void* wi, const void* wo, void* h,
+                             void* out, bool scatter_out, hipStream_t st, void* event_between);
 inline size_t expert_signbits_bytes(const moe_config& c) {
   return (size_t)c.E * c.G * c.C * c.H / 8;
 }

@@ -34,16 +34,30 @@ __global__ __launch_bounds__(256) void dispatch_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(
     const uint4* __restrict__ out, const int32_t* __restrict__ expert_idx,
-    const int32_t* __restrict__ slot, const float* __restrict__ weight, uint4* __restrict__ y,
-    int S, int G, int C, int vec_per_row, long long tokens) {
+    const int32_t* __restrict__ slot, const float* __restrict__ weight,
+    const int32_t* __restrict__ row_base, uint4* __restrict__ y,
+    int S, int G, int C, int E, int vec_per_row, long long tokens) {
   const long long n = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (n >= tokens) return;
   const int lane = threadIdx.x & 63;
   const int g = (int)(n / S);
   const int s0 = slot[2 * n], s1 = slot[2 * n + 1];
   const float w0 = weight[2 * n], w1 = weight[2 * n + 1];
-  const uint4* r0 = s0 >= 0 ? out + (((long long)expert_idx[2 * n] * G + g) * C + s0) * vec_per_row : nullptr;
-  const uint4* r1 = s1 >= 0 ? out + (((long long)expert_idx[2 * n + 1] * G + g) * C + s1) * vec_per_row : nullptr;
+  // row of a kept choice: (e G + g) C + slot in the [E,G,C,M] order, e G C + row_base[g,e] + slot
+  // in the packed order
+  const uint4 *r0 = nullptr, *r1 = nullptr;
+  if (s0 >= 0) {
+    const long long e = expert_idx[2 * n];
+    const long long row = row_base != nullptr ? e * G * C + row_base[(long long)g * E + e] + s0
+                                              : (e * G + g) * C + s0;
+    r0 = out + row * vec_per_row;
+  }
+  if (s1 >= 0) {
+    const long long e = expert_idx[2 * n + 1];
+    const long long row = row_base != nullptr ? e * G * C + row_base[(long long)g * E + e] + s1
+                                              : (e * G + g) * C + s1;
+    r1 = out + row * vec_per_row;
+  }
   uint4* dst = y + n * vec_per_row;
   constexpr int K = Vec16<T>::kElts;
   for (int v = lane; v < vec_per_row; v += 64) {
@@ -80,19 +94,20 @@ int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token
 }
 
 int launch_combine(const moe_config& c, const void* out, const int32_t* expert_idx,
-                   const int32_t* slot, const float* weight, void* y, hipStream_t st) {
+                   const int32_t* slot, const float* weight, const int32_t* row_base, void* y,
+                   hipStream_t st) {
   const int elt = c.act_dtype == MOE_F32 ? 4 : 2;
   const int vec_per_row = c.M * elt / 16;
   const long long tokens = (long long)c.G * c.S;
   const unsigned grid = (unsigned)((tokens + kRowsPerBlock - 1) / kRowsPerBlock);
   if (c.act_dtype == MOE_F32)
     hipLaunchKernelGGL(combine_kernel<float>, dim3(grid), dim3(256), 0, st,
-                       static_cast<const uint4*>(out), expert_idx, slot, weight,
-                       static_cast<uint4*>(y), c.S, c.G, c.C, vec_per_row, tokens);
+                       static_cast<const uint4*>(out), expert_idx, slot, weight, row_base,
+                       static_cast<uint4*>(y), c.S, c.G, c.C, c.E, vec_per_row, tokens);
   else
     hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(grid), dim3(256), 0, st,
-                       static_cast<const uint4*>(out), expert_idx, slot, weight,
-                       static_cast<uint4*>(y), c.S, c.G, c.C, vec_per_row, tokens);
+                       static_cast<const uint4*>(out), expert_idx, slot, weight, row_base,
+                       static_cast<uint4*>(y), c.S, c.G, c.C, c.E, vec_per_row, tokens);
   return check_launch();
 }
 

@@ -266,14 +266,21 @@ struct DmaSmem {
 // are the same tiling of the same [E,R,N] matrix, so no lane ever needs another lane's bits.
 // The reader fetches a tile's 8 KB into spare LDS with two register-bypassing copies issued
 // in the tile's first K step; the waits of the next two steps cover them.
-template <int ST, int EPI, bool GATHER, bool A_MNC, bool B_KC>
+// GATHER 2: the indices are absolute rows of the matrix A ([rows, K], row p of expert e comes
+// from row src_token[e * R + p], -1 = zero row): the packed row layout (RowPacking).
+// PACKED: expert e has only its first row_tile_start[e+1] - row_tile_start[e] row tiles multiplied
+// (the tiles of all experts are numbered consecutively in expert order; a block's tile numbers only
+// grow, so it finds a tile's expert by stepping a cursor forward).  SCATTER (with PACKED):
+// the rows of C go to the absolute rows src_token[e * R + p] of Cout ([rows, N]), -1 = not stored.
+template <int ST, int EPI, int GATHER, bool A_MNC, bool B_KC, bool PACKED, bool SCATTER>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
-    int R, int N, int K, int tiles_m, int tiles_n, int ntiles,
+    int R, int N, int K, int tiles_m, int tiles_n, int ntiles_static,
     const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
     uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask,
-    unsigned char* __restrict__ signbits) {
+    unsigned char* __restrict__ signbits, const int32_t* __restrict__ row_tile_start, int E) {
   static_assert(!(GATHER && A_MNC), "the gather form addresses whole rows of a K-contiguous A");
+  static_assert(!SCATTER || (PACKED && EPI == 0), "scattered rows: plain bf16 result of a packed launch");
   constexpr bool RELU = EPI == 1 || EPI == 4;
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
@@ -292,11 +299,32 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // XCD's L2 (a tall output, as in the weight gradients, would otherwise re-read its A panel
   // once per column tile).
   constexpr int kBand = 8;
-#define MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                    \
-  int rt_, ct_;                                                                              \
+  const int ntiles = PACKED ? row_tile_start[E] * tiles_n : ntiles_static;   // uniform
+  // PACKED: expert of the tile located last and its range of row tiles [rs, re) in the global
+  // numbering; one cursor for the copies (producer side), one for the epilogues
+  struct TileCursor { int e, rs, re; };
+  TileCursor pcur{-1, 0, 0}, ccur{-1, 0, 0};
+#define MOE_DMA_TILE(T_, CUR_, e_, rt_, ct_)                                                 \
+  int e_, rt_, ct_;                                                                          \
   {                                                                                          \
-    const int band_ = (t_) / (kBand * tiles_n), rem_ = (t_) - band_ * kBand * tiles_n;       \
-    const int left_ = tiles_m - band_ * kBand, rows_ = left_ < kBand ? left_ : kBand;        \
+    int t_, tm_;                                                                             \
+    if (PACKED) {                                                                            \
+      /* ends at the latest with e = E - 1: T_ < ntiles = row_tile_start[E] * tiles_n */     \
+      while ((T_) >= CUR_.re * tiles_n && CUR_.e + 1 < E) {                                  \
+        ++CUR_.e;                                                                            \
+        CUR_.rs = CUR_.re;                                                                   \
+        CUR_.re = row_tile_start[CUR_.e + 1];                                                \
+      }                                                                                      \
+      e_ = CUR_.e;                                                                           \
+      t_ = (T_) - CUR_.rs * tiles_n;                                                         \
+      tm_ = CUR_.re - CUR_.rs;                                                               \
+    } else {                                                                                 \
+      e_ = (T_) / per_e;                                                                     \
+      t_ = (T_) - e_ * per_e;                                                                \
+      tm_ = tiles_m;                                                                         \
+    }                                                                                        \
+    const int band_ = t_ / (kBand * tiles_n), rem_ = t_ - band_ * kBand * tiles_n;           \
+    const int left_ = tm_ - band_ * kBand, rows_ = left_ < kBand ? left_ : kBand;            \
     ct_ = rem_ / rows_;                                                                      \
     rt_ = band_ * kBand + (rem_ - ct_ * rows_);                                              \
   }
@@ -341,8 +369,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   typedef int __attribute__((address_space(3))) * lds_int_ptr;
 #define MOE_DMA_TOKENS(TILE)                                                                 \
   {                                                                                          \
-    const int e_ = (TILE) / per_e, t_ = (TILE) - e_ * per_e;                                 \
-    MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                        \
+    MOE_DMA_TILE(TILE, pcur, e_, rt_, ct_)                                                   \
     (void)ct_;                                                                               \
     const uint64_t ta_ = (uint64_t)(uintptr_t)(                                              \
         src_token + (size_t)e_ * R + (size_t)rt_ * BM + 64 * wave + lane);                   \
@@ -356,9 +383,14 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       const int tok_ = *(lds_int_ptr)(uintptr_t)(lds_tok + 4 * rl_);                         \
       const int row_ = 64 * wave + rl_;                                                      \
       const int ca_ = (lane & 3) ^ ((row_ >> 2) & 3);                                        \
-      const uint32_t n_ = (uint32_t)((m0_) + row_);                                          \
-      const uint32_t g_ = c_magic ? __umulhi(n_, c_magic) >> c_shift : n_;   /* n_ / C */    \
-      const bf16_t* src_ = tok_ >= 0 ? A + ((size_t)g_ * S + tok_) * K : zero_row;           \
+      const bf16_t* src_;                                                                    \
+      if (GATHER == 2) {                                                                     \
+        src_ = tok_ >= 0 ? A + (size_t)tok_ * K : zero_row;                                  \
+      } else {                                                                               \
+        const uint32_t n_ = (uint32_t)((m0_) + row_);                                        \
+        const uint32_t g_ = c_magic ? __umulhi(n_, c_magic) >> c_shift : n_; /* n_ / C */    \
+        src_ = tok_ >= 0 ? A + ((size_t)g_ * S + tok_) * K : zero_row;                       \
+      }                                                                                      \
       a_addr[q] = (uint64_t)(uintptr_t)(src_ + 8 * ca_);                                     \
     }                                                                                        \
   }
@@ -369,8 +401,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   if (GATHER) { MOE_DMA16_ADDR(LDS_U32, a_addr[q]); } else { MOE_DMA16(LDS_U32, a_voff[q], p_a); }
 #define MOE_DMA_SET_SOURCES()                                                                \
   {                                                                                          \
-    const int e_ = p_tile / per_e, t_ = p_tile - e_ * per_e;                                 \
-    MOE_DMA_TILE_COORDS(t_, rt_, ct_)                                                        \
+    MOE_DMA_TILE(p_tile, pcur, e_, rt_, ct_)                                                 \
     if (GATHER) MOE_DMA_GATHER_ROWS(e_, rt_ * BM)                                            \
     else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)rt_ * BM;                         \
     else p_a = A + ((size_t)e_ * R + (size_t)rt_ * BM) * K;                                  \
@@ -492,8 +523,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       else if (younger == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       __syncthreads();
       if (EPI == 5 && kt == 0) {
-        const int e5 = c_tile / per_e, t5 = c_tile - e5 * per_e;
-        MOE_DMA_TILE_COORDS(t5, rt5, ct5)
+        MOE_DMA_TILE(c_tile, ccur, e5, rt5, ct5)
         const unsigned char* src5 = signbits + ((size_t)(e5 * tiles_m + rt5) * tiles_n + ct5) * 8192 +
                                     wave * 2048 + lane * 16;
         MOE_DMA16_ADDR(lds_bits, (uint64_t)(uintptr_t)src5);
@@ -526,8 +556,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     // row r at position c ^ (r & 15), its two 8-byte halves swapped when r >= 16 (then the
     // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // every copy issued so far
-    const int e = c_tile / per_e, t = c_tile - e * per_e;
-    MOE_DMA_TILE_COORDS(t, rt, ct)
+    MOE_DMA_TILE(c_tile, ccur, e, rt, ct)
     const int m0 = rt * BM, n0 = ct * BN;
     const size_t c_off = ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
     bf16_t* Ce = Cout + c_off;
@@ -560,6 +589,12 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+      int drow[8];                                             // SCATTER: destination rows
+      if (SCATTER) {
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps)
+          drow[ps] = src_token[(size_t)e * R + m0 + wm0 + 32 * i + 4 * ps + (lane >> 4)];
+      }
       u32x4_t mk[8];
       if (EPI == 2) {
 #pragma unroll
@@ -599,7 +634,12 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
           for (int w = 0; w < 4; ++w)
             d[w] &= ((byte >> (2 * w)) & 1u ? 0xffffu : 0u) | ((byte >> (2 * w + 1)) & 1u ? 0xffff0000u : 0u);
         }
-        *reinterpret_cast<u32x4_t*>(Ce + (size_t)(32 * i + rr) * N + 8 * c) = d;
+        if (SCATTER) {
+          if (drow[ps] >= 0)
+            *reinterpret_cast<u32x4_t*>(Cout + (size_t)drow[ps] * N + n0 + wn0 + 8 * c) = d;
+        } else {
+          *reinterpret_cast<u32x4_t*>(Ce + (size_t)(32 * i + rr) * N + 8 * c) = d;
+        }
       }
       __builtin_amdgcn_sched_barrier(0);   // one row group at a time: small register need
     }
@@ -611,7 +651,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
   }
 #undef MOE_DMA_SET_SOURCES
-#undef MOE_DMA_TILE_COORDS
+#undef MOE_DMA_TILE
 #undef MOE_DMA_GATHER_ROWS
 #undef MOE_DMA_TOKENS
 #undef MOE_DMA16_ADDR
@@ -624,10 +664,12 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #undef MOE_DMA_MFMA_ROW
 }
 
-template <int ST, int EPI, bool GATHER, bool A_MNC = false, bool B_KC = false>
+template <int ST, int EPI, int GATHER, bool A_MNC = false, bool B_KC = false, bool PACKED = false,
+          bool SCATTER = false>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
                     const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st,
-                    const bf16_t* mask = nullptr, unsigned char* signbits = nullptr) {
+                    const bf16_t* mask = nullptr, unsigned char* signbits = nullptr,
+                    const int32_t* row_tile_start = nullptr) {
   using SM = DmaSmem<ST>;
   static_assert(!(GATHER && EPI == 5), "the two users of the spare LDS exclude each other");
   constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0) + (EPI == 5 ? 8192 : 0);
@@ -635,13 +677,14 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   // l = ceil(log2 C); C == 1 is flagged by c_magic == 0
   uint32_t c_magic = 0;
   int c_shift = 0;
-  if (GATHER && C > 1) {
+  if (GATHER == 1 && C > 1) {
     int l = 0;
     while ((1LL << l) < C) ++l;
     c_magic = (uint32_t)((((unsigned long long)1 << (31 + l)) + C - 1) / C);
     c_shift = l - 1;
   }
-  auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC>;
+  if (PACKED && row_tile_start == nullptr) return MOE_EINVAL;
+  auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER>;
   // per device, once: the kernel's LDS limit and the number of compute units.  The cached
   // values are constants of the device, so a race between two first calls is harmless.
   static int cus_of[kMaxDevices] = {};
@@ -661,7 +704,8 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
-                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask, signbits);
+                     tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask, signbits,
+                     row_tile_start, E);
   return check_launch();
 }
 
@@ -705,7 +749,7 @@ template <bool RELU>
 int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
               hipStream_t st) {
   if (dma_shape_ok(R, N, K))
-    return launch_bf16_dma<4, RELU ? 1 : 0, false>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0,
+    return launch_bf16_dma<4, RELU ? 1 : 0, 0>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0,
                                                    st);
   if (R > 128 && N >= 256) return launch_bf16<256, 256, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
   return launch_bf16<128, 128, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
@@ -756,8 +800,8 @@ int launch_gemm_bf16_f32out(bool transposed_a, const void* A, const void* B, flo
   auto c = reinterpret_cast<bf16_t*>(Cout);
   // transposed_a: C = A^T . B with A [K,R], B [K,N];  else C = A . B^T with A [R,K], B [N,K]
   return transposed_a
-             ? launch_bf16_dma<4, 3, false, true, false>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st)
-             : launch_bf16_dma<4, 3, false, false, true>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st);
+             ? launch_bf16_dma<4, 3, 0, true, false>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st)
+             : launch_bf16_dma<4, 3, 0, false, true>(a, b, c, batch, R, N, K, nullptr, nullptr, 0, 0, st);
 }
 
 bool expert_gemm1_can_gather(const moe_config& c) {
@@ -772,13 +816,43 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
                                hipStream_t st) {
   if (!expert_gemm1_can_gather(c)) return MOE_EUNSUPPORTED;
   if (signbits != nullptr)
-    return launch_bf16_dma<4, 4, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
+    return launch_bf16_dma<4, 4, 1>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
                                        static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
                                        static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr,
                                        static_cast<unsigned char*>(signbits));
-  return launch_bf16_dma<4, 1, true>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
+  return launch_bf16_dma<4, 1, 1>(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(wi),
                                         static_cast<bf16_t*>(h), c.E, c.G * c.C, c.H, c.M, src_token,
                                         static_cast<const bf16_t*>(zero_row), c.S, c.C, st);
+}
+
+// Packed row layout: both GEMMs walk the list of occupied row tiles.  The first gathers its rows
+// through pk.packed_src (absolute rows of `a`: token rows of x, or rows of an [E,G,C,M] buffer),
+// h and (scatter_out == false) out hold packed rows; scatter_out sends the rows of out back to
+// the absolute rows pk.packed_src names.
+int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
+                             const void* zero_row, const void* wi, const void* wo, void* h,
+                             void* out, bool scatter_out, hipStream_t st, void* event_between) {
+  if (!expert_gemm1_can_gather(c) || !dma_shape_ok(c.G * c.C, c.M, c.H)) return MOE_EUNSUPPORTED;
+  const int R = c.G * c.C;
+  int rc = launch_bf16_dma<4, 1, 2, false, false, true>(
+      static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(h), c.E, R,
+      c.H, c.M, pk.packed_src, static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr, nullptr,
+      pk.row_tile_start);
+  if (rc != MOE_OK) return rc;
+  if (event_between != nullptr &&
+      hipEventRecord(static_cast<hipEvent_t>(event_between), st) != hipSuccess)
+    return MOE_EHIP;
+  if (scatter_out)
+    return launch_bf16_dma<4, 0, 0, false, false, true, true>(
+        static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E,
+        R, c.M, c.H, pk.packed_src, nullptr, 0, 0, st, nullptr, nullptr, pk.row_tile_start);
+  return launch_bf16_dma<4, 0, 0, false, false, true, false>(
+      static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E, R,
+      c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, pk.row_tile_start);
+}
+
+bool expert_ffn_can_pack(const moe_config& c) {
+  return expert_gemm1_can_gather(c) && dma_shape_ok(c.G * c.C, c.M, c.H);
 }
 
 int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,
@@ -799,12 +873,12 @@ int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, 
   const long long R = (long long)c.G * c.C;
   // the forward pass recorded the sign bits exactly when its first GEMM gathered (K >= 128)
   if (signbits != nullptr && expert_gemm1_can_gather(c))
-    return launch_bf16_dma<4, 5, false, false, true>(
+    return launch_bf16_dma<4, 5, 0, false, true>(
         static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
         c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, nullptr,
         const_cast<unsigned char*>(static_cast<const unsigned char*>(signbits)));
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.H, c.M))
-    return launch_bf16_dma<4, 2, false, false, true>(
+    return launch_bf16_dma<4, 2, 0, false, true>(
         static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
         c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, static_cast<const bf16_t*>(h));
   return launch_gemm_strided(c, 2, dout, R * c.M, c.M, 1, wo, (long long)c.H * c.M, 1, c.M, dh, h,
@@ -815,7 +889,7 @@ int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, v
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.H, c.M, (int)R))
-    return launch_bf16_dma<4, 0, false, true, false>(
+    return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dwo),
         c.E, c.H, c.M, (int)R, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, h, R * c.H, 1, c.H, dout, R * c.M, c.M, 1, dwo, nullptr, c.H,
@@ -826,7 +900,7 @@ int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, vo
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.M, c.H))
-    return launch_bf16_dma<4, 0, false, false, true>(
+    return launch_bf16_dma<4, 0, 0, false, true>(
         static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(dbuf),
         c.E, (int)R, c.M, c.H, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, dh, R * c.H, c.H, 1, wi, (long long)c.M * c.H, 1, c.H, dbuf,
@@ -837,7 +911,7 @@ int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, v
                          hipStream_t st) {
   const long long R = (long long)c.G * c.C;
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.M, c.H, (int)R))
-    return launch_bf16_dma<4, 0, false, true, false>(
+    return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dwi),
         c.E, c.M, c.H, (int)R, nullptr, nullptr, 0, 0, st);
   return launch_gemm_strided(c, 0, buf, R * c.M, 1, c.M, dh, R * c.H, c.H, 1, dwi, nullptr, c.M,

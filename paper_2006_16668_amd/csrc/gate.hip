@@ -746,16 +746,60 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(
   for (int c = f + k; c < C; c += 8) st[c] = -1;
 }
 
-// One wavefront per chunk.
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Book-keeping of the packed row layout (see RowPacking), shared by the two kernels that build
+// the maps; called by one wavefront per block, b = block index of nb blocks:
+//   - the rows between an expert's last kept row and the end of its last 256-row tile get the
+//     source -1 (they are multiplied as zero rows and never read back);
+//   - block 0 writes the running count of occupied 256-row tiles over the experts,
+//     row_tile_start[e] = sum over e' < e of ceil(kept_e' / 256), and the total at index E.
+__device__ __forceinline__ void pack_bookkeeping(int b, int nb, int lane, int G, int E, int R,
+                                                 const int32_t* __restrict__ fill, const RowPacking& pk) {
+  for (int e = b; e < E; e += nb) {
+    int kept = 0;
+    for (int g = lane; g < G; g += 64) kept += fill[(size_t)g * E + e];
+    kept = wave_sum_int(kept);
+    const int end = (kept + 255) / 256 * 256;          // <= R: kept <= R and R % 256 == 0
+    for (int p = kept + lane; p < end; p += 64) pk.packed_src[(size_t)e * R + p] = -1;
+  }
+  if (b == 0) {
+    int run = 0;
+    for (int e0 = 0; e0 < E; e0 += 64) {
+      const int e = e0 + lane;
+      int kept = 0;
+      if (e < E)
+        for (int g = 0; g < G; ++g) kept += fill[(size_t)g * E + e];
+      const int nt = (kept + 255) / 256;
+      int incl = nt;                                     // inclusive scan over the lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      if (e < E) pk.row_tile_start[e] = run + incl - nt;
+      run += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) pk.row_tile_start[E] = run;
+  }
+}
+
+// One wavefront per chunk.  pk.packed_src != NULL: also builds the packed row layout of the
+// expert GEMMs (row of a kept choice = kept rows of the same expert in earlier groups + slot).
 __global__ __launch_bounds__(64) void gate_slots_kernel(
     int S, int E, int C, int G, int nch,
     const int32_t* __restrict__ base1, const int32_t* __restrict__ base2,
     const int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot,
     float* __restrict__ weight, int32_t* __restrict__ src_token,
     const int32_t* __restrict__ c1, const float* __restrict__ mean_gate, float* __restrict__ aux,
-    uint32_t* __restrict__ zero_fill, int zero_words) {
+    uint32_t* __restrict__ zero_fill, int zero_words, const int32_t* __restrict__ fill, RowPacking pk) {
   const int g = blockIdx.x / nch, ch = blockIdx.x % nch;
   const int lane = threadIdx.x;
+  const bool packing = pk.packed_src != nullptr;
   // optional: clear the all-zero activation row that stands in for empty expert slots when
   // the first expert GEMM gathers its rows from x
   if (blockIdx.x == 0)
@@ -767,7 +811,14 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
       part += ((float)c1[(size_t)g * E + e] / (float)S) * mean_gate[(size_t)g * E + e];
     part = wave_sum(part);
     if (lane == 0) aux[g] = part / (float)E;
+    if (packing)
+      for (int e = lane; e < E; e += 64) {
+        int rb = 0;
+        for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
+        pk.row_base[(size_t)g * E + e] = rb;
+      }
   }
+  if (packing) pack_bookkeeping(blockIdx.x, gridDim.x, lane, G, E, G * C, fill, pk);
   const int s = ch * kChunk + lane;
   const bool valid = s < S;
   const size_t n = (size_t)g * S + (valid ? s : 0);
@@ -802,6 +853,40 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
   if (s2 < 0) weight[2 * n + 1] = 0.f;
   if (s1 >= 0) src_token[((size_t)e1 * G + g) * C + s1] = s;
   if (s2 >= 0) src_token[((size_t)e2 * G + g) * C + s2] = s;
+  if (packing) {
+    const size_t R = (size_t)G * C;
+    int rb1 = 0, rb2 = 0;
+    for (int gg = 0; gg < g; ++gg) {
+      if (s1 >= 0) rb1 += fill[(size_t)gg * E + e1];
+      if (s2 >= 0) rb2 += fill[(size_t)gg * E + e2];
+    }
+    if (s1 >= 0) pk.packed_src[(size_t)e1 * R + rb1 + s1] = (int32_t)n;
+    if (s2 >= 0) pk.packed_src[(size_t)e2 * R + rb2 + s2] = (int32_t)n;
+  }
+}
+
+// The packed row layout from fill alone, for expert buffers in the [E,G,C,M] order of the staged
+// entry points: row p of expert e comes from (and goes back to) row (e G + g) C + c of the buffer.
+__global__ __launch_bounds__(64) void row_maps_from_fill_kernel(
+    int E, int G, int C, const int32_t* __restrict__ fill, RowPacking pk,
+    uint32_t* __restrict__ zero_fill, int zero_words) {
+  const int lane = threadIdx.x;
+  if (blockIdx.x == 0)
+    for (int i = lane; i < zero_words; i += 64) zero_fill[i] = 0u;
+  const size_t R = (size_t)G * C;
+  pack_bookkeeping(blockIdx.x, gridDim.x, lane, G, E, (int)R, fill, pk);
+  const long long idx = (long long)blockIdx.x * 64 + lane;
+  if (idx >= (long long)E * G * C) return;
+  const int c = (int)(idx % C), g = (int)((idx / C) % G), e = (int)(idx / ((long long)C * G));
+  if (c == 0) {
+    int rb = 0;
+    for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
+    pk.row_base[(size_t)g * E + e] = rb;
+  }
+  if (c >= fill[(size_t)g * E + e]) return;
+  int rb = 0;
+  for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
+  pk.packed_src[(size_t)e * R + rb + c] = (int32_t)idx;
 }
 
 template <typename T, bool PRE = false>
@@ -914,7 +999,8 @@ size_t gate_workspace_bytes(const moe_config& c) {
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
-                float* gates_opt, void* ws, void* zero_row, hipStream_t st) {
+                float* gates_opt, void* ws, void* zero_row, const RowPacking* packing,
+                hipStream_t st) {
   const int nch = (c.S + kChunk - 1) / kChunk;
   const size_t seg = align_up((size_t)c.G * nch * c.E * 4, 256);
   int32_t* hist1 = reinterpret_cast<int32_t*>(ws);
@@ -993,6 +1079,16 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
   hipLaunchKernelGGL(gate_slots_kernel, dim3((unsigned)(c.G * nch)), dim3(64), 0, st, c.S, c.E,
                      c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token, c1,
                      mean_gate, aux, static_cast<uint32_t*>(zero_row),
+                     zero_row != nullptr ? c.M / 2 : 0, fill,
+                     packing != nullptr ? *packing : RowPacking{nullptr, nullptr, nullptr});
+  return check_launch();
+}
+
+int launch_row_maps_from_fill(const moe_config& c, const int32_t* fill, const RowPacking& pk,
+                              void* zero_row, hipStream_t st) {
+  const long long slots = (long long)c.E * c.G * c.C;
+  hipLaunchKernelGGL(row_maps_from_fill_kernel, dim3((unsigned)((slots + 63) / 64)), dim3(64), 0, st,
+                     c.E, c.G, c.C, fill, pk, static_cast<uint32_t*>(zero_row),
                      zero_row != nullptr ? c.M / 2 : 0);
   return check_launch();
 }

@@ -62,6 +62,17 @@ SMALL_CASES = [
     # columns and K (rows per expert = 303, no multiple of 4 either)
     MoEConfig("f32_tiles", G=3, S=200, M=136, H=264, E=3, C=101, act_dtype="f32", seed=37),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
+    # the layer call packs the occupied rows of an expert to the front of its block and multiplies
+    # only the 256-row tiles that hold them: skewed routing (full and nearly empty experts), far
+    # more capacity than tokens (one tile of several per expert), experts that receive nothing,
+    # many groups with few slots each, a row-tile count that straddles bands of eight
+    MoEConfig("packed_skew", G=8, S=512, M=256, H=256, E=16, C=64, act_dtype="bf16", seed=38,
+              logit_bias_std=1.0),
+    MoEConfig("packed_sparse", G=4, S=64, M=256, H=512, E=8, C=192, act_dtype="bf16", seed=39),
+    MoEConfig("packed_empty_experts", G=2, S=8, M=256, H=256, E=32, C=128, act_dtype="bf16", seed=40),
+    MoEConfig("packed_c16", G=16, S=160, M=256, H=256, E=20, C=16, act_dtype="bf16", seed=46),
+    MoEConfig("packed_bands", G=4, S=1500, M=256, H=512, E=5, C=704, act_dtype="bf16", seed=47,
+              logit_bias_std=0.7),
 ]
 
 
@@ -116,6 +127,21 @@ def test_stages_and_layer_match_oracle(cfg):
     y2, aux2 = gpu_forward(cfg, inp)
     assert torch.equal(y2, y)
     assert torch.equal(aux2, r["aux"])
+
+    # --- experts again with fill and a workspace: occupied rows only.  Same bits in every
+    # occupied slot; where the kernels pack (moe_forward_packs_rows) the other slots of out are
+    # not written, elsewhere the call is the one above
+    out2 = torch.full((cfg.E, cfg.G, cfg.C, cfg.M), 77.0, dtype=sh.torch_dtype, device=DEV)
+    h2 = torch.empty_like(h)
+    fws = torch.empty(max(moe.moe_expert_ffn_workspace_bytes(sh), 256), dtype=torch.uint8, device=DEV)
+    moe.moe_expert_ffn(sh, buf, inp.wi, inp.wo, h2, out2, fill=r["fill"], ws=fws)
+    torch.cuda.synchronize()
+    occ_t = torch.from_numpy(occ).to(DEV)
+    assert torch.equal(out2[occ_t], out[occ_t])
+    if moe.moe_forward_packs_rows(sh):
+        assert (out2[~occ_t] == 77.0).all()
+    else:
+        assert torch.equal(out2, out)
 
 
 def test_combine_is_exact_gather_for_identity_like_inputs():
