@@ -95,6 +95,28 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
              float* gates_opt, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The gate weights in the form the logit kernels multiply (Algorithm 2, line 1: the GSM,ME->GSE
+ * projection).  bf16 layers compute the logits on the matrix cores with wg split into three bf16
+ * terms (hi + mid + lo = all 24 mantissa bits, so every product with a bf16 activation is exact)
+ * laid out in the order of the MFMA operand; moe_gate and moe_forward build that form from wg
+ * on every call.  wg is a parameter, so a caller can build it once per weight update instead:
+ *   moe_gate_pack_bytes   size of the packed form for this config (0: this gate reads wg as it
+ *                         is and the calls below take wg_packed == NULL).  Pure host function.
+ *   moe_gate_pack         wg [M,E] fp32 -> wg_packed (caller-owned, 256-byte aligned)
+ *   moe_gate_prepacked    moe_gate        that reads wg_packed instead of packing wg
+ *   moe_forward_prepacked moe_forward_events (events may be NULL) likewise
+ * Results are bit-identical to moe_gate / moe_forward with the same wg.  The library keeps no
+ * record of the buffer: passing a wg_packed that was built from other weights, or for another
+ * config, gives the logits of those weights.
+ */
+int moe_gate_pack_bytes(const moe_config* cfg, size_t* bytes);
+int moe_gate_pack(const moe_config* cfg, const float* wg, void* wg_packed, void* stream);
+int moe_gate_prepacked(const moe_config* cfg, const void* x, const float* wg, const void* wg_packed,
+                       const float* u, int32_t* expert_idx, int32_t* slot, float* weight,
+                       int32_t* fill, int32_t* src_token, int32_t* c1, float* mean_gate,
+                       float* aux, float* gates_opt, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * moe_gate for callers that cannot allocate device memory and have no workspace to pass:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments (minus ws / ws_bytes), same kernels and bit-identical results; the scratch memory
@@ -201,6 +223,12 @@ int moe_forward_packs_rows(const moe_config* cfg, int* packed);
 int moe_forward_events(const moe_config* cfg, const void* x, const float* wg, const float* u,
                        const void* wi, const void* wo, void* y, float* aux,
                        void* ws, size_t ws_bytes, void* stream, void* const* events);
+
+/* moe_forward_events with pre-packed gate weights (see moe_gate_pack). */
+int moe_forward_prepacked(const moe_config* cfg, const void* x, const float* wg,
+                          const void* wg_packed, const float* u, const void* wi, const void* wo,
+                          void* y, float* aux, void* ws, size_t ws_bytes, void* stream,
+                          void* const* events);
 
 /*
  * ---- Backward pass -------------------------------------------------------------

@@ -22,6 +22,7 @@ SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
 EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
            "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_dispatch",
+           "moe_gate_pack_bytes", "moe_gate_pack", "moe_gate_prepacked", "moe_forward_prepacked",
            "moe_expert_ffn_workspace_bytes", "moe_forward_packs_rows", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
            "moe_forward_fuses_dispatch", "moe_forward_train", "moe_backward_workspace_bytes",
            "moe_backward", "moe_backward_events", "moe_add_layer_norm",
@@ -110,6 +111,10 @@ def load_library() -> ctypes.CDLL:
         "moe_forward_fuses_dispatch": [cfgp, ctypes.POINTER(i32)],
         "moe_gate": [cfgp] + [vp] * 13 + [sz, vp],
         "moe_gate_noalloc": [cfgp] + [vp] * 13,
+        "moe_gate_pack_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_gate_pack": [cfgp, vp, vp, vp],
+        "moe_gate_prepacked": [cfgp] + [vp] * 14 + [sz, vp],
+        "moe_forward_prepacked": [cfgp] + [vp] * 9 + [sz, vp, ctypes.POINTER(ctypes.c_void_p)],
         "moe_gate_noalloc_max_bytes": [ctypes.POINTER(sz)],
         "moe_dispatch": [cfgp, vp, vp, vp, vp],
         "moe_expert_ffn": [cfgp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
@@ -218,6 +223,58 @@ def moe_gate(shape: MoEShape, x, wg, u, expert_idx, slot, weight, fill, src_toke
         _ptr(c1, i32, (G, E), "c1"), _ptr(mean_gate, f32, (G, E), "mean_gate"),
         _ptr(aux, f32, (G,), "aux"), _ptr(gates_opt, f32, (G, S, E), "gates_opt"),
         wsp, wsn, _stream()), "moe_gate")
+
+
+def moe_gate_pack_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_gate_pack_bytes(ctypes.byref(c), ctypes.byref(n)), "moe_gate_pack_bytes")
+    return n.value
+
+
+def moe_gate_pack(shape: MoEShape, wg, wg_packed):
+    """wg [M,E] fp32 -> wg_packed (uint8 tensor of moe_gate_pack_bytes, or None when that is 0)."""
+    c = shape._c()
+    dst = _ws(wg_packed, "wg_packed")[0] if wg_packed is not None else None
+    _check(load_library().moe_gate_pack(
+        ctypes.byref(c), _ptr(wg, torch.float32, (shape.M, shape.E), "wg"), dst, _stream()),
+        "moe_gate_pack")
+
+
+def moe_gate_prepacked(shape: MoEShape, x, wg, wg_packed, u, expert_idx, slot, weight, fill, src_token,
+                       c1, mean_gate, aux, gates_opt, ws):
+    G, S, M, E, C = shape.G, shape.S, shape.M, shape.E, shape.C
+    i32, f32 = torch.int32, torch.float32
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    pk = _ws(wg_packed, "wg_packed")[0] if wg_packed is not None else None
+    _check(load_library().moe_gate_prepacked(
+        ctypes.byref(c), _ptr(x, shape.torch_dtype, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"), pk,
+        _ptr(u, f32, (G, S), "u"), _ptr(expert_idx, i32, (G, S, 2), "expert_idx"),
+        _ptr(slot, i32, (G, S, 2), "slot"), _ptr(weight, f32, (G, S, 2), "weight"),
+        _ptr(fill, i32, (G, E), "fill"), _ptr(src_token, i32, (E, G, C), "src_token"),
+        _ptr(c1, i32, (G, E), "c1"), _ptr(mean_gate, f32, (G, E), "mean_gate"),
+        _ptr(aux, f32, (G,), "aux"), _ptr(gates_opt, f32, (G, S, E), "gates_opt"),
+        wsp, wsn, _stream()), "moe_gate_prepacked")
+
+
+def moe_forward_prepacked(shape: MoEShape, x, wg, wg_packed, u, wi, wo, y, aux, ws, events=None):
+    """moe_forward (events=None) / moe_forward_events with gate weights packed by moe_gate_pack."""
+    G, S, M, H, E = shape.G, shape.S, shape.M, shape.H, shape.E
+    dt, f32 = shape.torch_dtype, torch.float32
+    handles = None
+    if events is not None:
+        if len(events) != FORWARD_EVENTS:
+            raise ValueError(f"need {FORWARD_EVENTS} events")
+        handles = (ctypes.c_void_p * FORWARD_EVENTS)(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    c = shape._c()
+    wsp, wsn = _ws(ws)
+    pk = _ws(wg_packed, "wg_packed")[0] if wg_packed is not None else None
+    _check(load_library().moe_forward_prepacked(
+        ctypes.byref(c), _ptr(x, dt, (G, S, M), "x"), _ptr(wg, f32, (M, E), "wg"), pk,
+        _ptr(u, f32, (G, S), "u"), _ptr(wi, dt, (E, M, H), "wi"), _ptr(wo, dt, (E, H, M), "wo"),
+        _ptr(y, dt, (G, S, M), "y"), _ptr(aux, f32, (G,), "aux"), wsp, wsn, _stream(), handles),
+        "moe_forward_prepacked")
 
 
 def moe_gate_noalloc_max_bytes() -> int:

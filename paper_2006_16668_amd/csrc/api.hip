@@ -104,7 +104,8 @@ BackwardWs carve_bwd(const moe_config& c) {
 
 int forward_impl(const moe_config* cfg, const void* x, const float* wg, const float* u,
                  const void* wi, const void* wo, void* y, float* aux, void* ws, size_t ws_bytes,
-                 void* stream, void* const* events, bool keep_gates) {
+                 void* stream, void* const* events, bool keep_gates,
+                 const void* wg_packed = nullptr) {
   int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
   const void* req[] = {x, wg, u, wi, wo, y, aux, ws};
@@ -140,14 +141,15 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
                         reinterpret_cast<float*>(base + w.mean_gate), aux,
                         keep_gates ? reinterpret_cast<float*>(base + w.gates) : nullptr,
                         base + w.gate_ws, gather ? base + w.zero_row : nullptr,
-                        packed ? &pk : nullptr, st);
+                        packed ? &pk : nullptr, wg_packed, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
   if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
   if (packed) {
-    rc = moe::launch_expert_ffn_packed(*cfg, x, pk, base + w.zero_row, wi, wo, base + w.h,
+    rc = moe::launch_expert_ffn_packed(*cfg, x, pk, reinterpret_cast<const int32_t*>(base + w.fill),
+                                       base + w.zero_row, wi, wo, base + w.h,
                                        base + w.out, false, st, events != nullptr ? events[3] : nullptr);
     if (rc != MOE_OK) return rc;
   } else {
@@ -359,6 +361,54 @@ int moe_forward_fuses_dispatch(const moe_config* cfg, int* fused) {
   return MOE_OK;
 }
 
+int moe_gate_pack_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = moe::gate_pack_bytes(*cfg);
+  return MOE_OK;
+}
+
+int moe_gate_pack(const moe_config* cfg, const float* wg, void* wg_packed, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (wg == nullptr || !aligned16(wg)) return MOE_EINVAL;
+  if (moe::gate_pack_bytes(*cfg) == 0) return MOE_OK;
+  if (wg_packed == nullptr || (reinterpret_cast<uintptr_t>(wg_packed) & 255u) != 0) return MOE_EINVAL;
+  return moe::launch_gate_pack(*cfg, wg, wg_packed, static_cast<hipStream_t>(stream));
+}
+
+int moe_forward_prepacked(const moe_config* cfg, const void* x, const float* wg,
+                          const void* wg_packed, const float* u, const void* wi, const void* wo,
+                          void* y, float* aux, void* ws, size_t ws_bytes, void* stream,
+                          void* const* events) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (moe::gate_pack_bytes(*cfg) == 0) wg_packed = nullptr;       // this gate reads wg itself
+  else if (wg_packed == nullptr || (reinterpret_cast<uintptr_t>(wg_packed) & 255u) != 0)
+    return MOE_EINVAL;
+  return forward_impl(cfg, x, wg, u, wi, wo, y, aux, ws, ws_bytes, stream, events, false, wg_packed);
+}
+
+int moe_gate_prepacked(const moe_config* cfg, const void* x, const float* wg, const void* wg_packed,
+                       const float* u, int32_t* expert_idx, int32_t* slot, float* weight,
+                       int32_t* fill, int32_t* src_token, int32_t* c1, float* mean_gate,
+                       float* aux, float* gates_opt, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  const void* req[] = {x, wg, u, expert_idx, slot, weight, fill, src_token, c1, mean_gate, aux, ws};
+  for (const void* p : req)
+    if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
+  if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
+  if (moe::gate_pack_bytes(*cfg) == 0) wg_packed = nullptr;
+  else if (wg_packed == nullptr || (reinterpret_cast<uintptr_t>(wg_packed) & 255u) != 0)
+    return MOE_EINVAL;
+  if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
+  return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
+                          mean_gate, aux, gates_opt, ws, nullptr, nullptr, wg_packed,
+                          static_cast<hipStream_t>(stream));
+}
+
 int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float* u,
              int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
              int32_t* src_token, int32_t* c1, float* mean_gate, float* aux, float* gates_opt,
@@ -371,7 +421,7 @@ int moe_gate(const moe_config* cfg, const void* x, const float* wg, const float*
   if (gates_opt != nullptr && !aligned16(gates_opt)) return MOE_EINVAL;
   if (ws_bytes < moe::gate_workspace_bytes(*cfg)) return MOE_EWORKSPACE;
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
-                          mean_gate, aux, gates_opt, ws, nullptr, nullptr,
+                          mean_gate, aux, gates_opt, ws, nullptr, nullptr, nullptr,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -398,7 +448,7 @@ int moe_gate_noalloc(const moe_config* cfg, const void* x, const float* wg, cons
   // every word of the scratch that the kernels read is written earlier in the same call
   // (chunk histograms, gate sums and the packed weights), so nothing has to be cleared
   return moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight, fill, src_token, c1,
-                          mean_gate, aux, gates_opt, ws, nullptr, nullptr,
+                          mean_gate, aux, gates_opt, ws, nullptr, nullptr, nullptr,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -449,7 +499,8 @@ int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, 
     void* zero_row = static_cast<char*>(ws) + maps;
     int r = moe::launch_row_maps_from_fill(*cfg, fill, pk, zero_row, st);
     if (r != MOE_OK) return r;
-    return moe::launch_expert_ffn_packed(*cfg, buf, pk, zero_row, wi, wo, h_ws, out, true, st, nullptr);
+    return moe::launch_expert_ffn_packed(*cfg, buf, pk, fill, zero_row, wi, wo, h_ws, out, true, st,
+                                         nullptr);
   }
   const int rc1 = moe::launch_expert_gemm1(*cfg, buf, wi, h_ws, st);
   if (rc1 != MOE_OK) return rc1;

@@ -89,19 +89,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // Packed row layout of the expert GEMMs (Section 2.2, "Expert capacity": a buffer position holds
 // a token or nothing, and FFN_e(0) = 0, so positions that hold nothing need not be multiplied).
-// The kept rows of expert e, in (group, slot) order, occupy rows 0 .. kept_e - 1 of its block of
-// R = G*C rows; only the ceil(kept_e / 256) row tiles that hold them are multiplied.
+// The kept rows of expert e (kept_e = sum over g of fill[g,e]), in (group, slot) order, occupy
+// rows 0 .. kept_e - 1 of its block of R = G*C rows; only the ceil(kept_e / 256) row tiles that
+// hold them are multiplied.  The GEMM kernels derive kept_e and the tile counts from fill.
 struct RowPacking {
   int32_t* row_base;     // [G,E]  kept rows of expert e in the groups before g
-  int32_t* packed_src;   // [E,R]  source row of packed row p (a row index into the A operand's
-                         //        matrix), -1 from kept_e to the end of the last occupied tile;
-                         //        rows of unoccupied tiles are not written
-  int32_t* row_tile_start;  // [E+1] occupied 256-row tiles of the experts before e; [E] = total
+  int32_t* packed_src;   // [E,R]  source row of packed row p < kept_e (a row index into the A
+                         //        operand's matrix); entries from kept_e on are not written
 };
-inline size_t row_packing_bytes(const moe_config& c) {      // the three arrays, each 256-aligned
+inline size_t row_packing_bytes(const moe_config& c) {      // both arrays, each 256-aligned
   const size_t rows = (size_t)c.E * c.G * c.C;
-  return align_up((size_t)c.G * c.E * 4, 256) + align_up(rows * 4, 256) +
-         align_up(((size_t)c.E + 1) * 4, 256);
+  return align_up((size_t)c.G * c.E * 4, 256) + align_up(rows * 4, 256);
 }
 inline RowPacking carve_row_packing(const moe_config& c, void* base) {
   const size_t rows = (size_t)c.E * c.G * c.C;
@@ -110,8 +108,7 @@ inline RowPacking carve_row_packing(const moe_config& c, void* base) {
   pk.row_base = reinterpret_cast<int32_t*>(p);
   p += align_up((size_t)c.G * c.E * 4, 256);
   pk.packed_src = reinterpret_cast<int32_t*>(p);
-  p += align_up(rows * 4, 256);
-  pk.row_tile_start = reinterpret_cast<int32_t*>(p);
+  (void)rows;
   return pk;
 }
 
@@ -123,7 +120,11 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
                 float* gates_opt, void* ws, void* zero_row, const RowPacking* packing,
-                hipStream_t st);
+                const void* wg_prepacked, hipStream_t st);
+// wg in the form the logit kernels multiply (gate_pack_bytes may be 0: nothing to pack);
+// wg_prepacked of launch_gate: NULL, or the result of launch_gate_pack for the same config and wg
+size_t gate_pack_bytes(const moe_config& c);
+int launch_gate_pack(const moe_config& c, const float* wg, void* packed, hipStream_t st);
 // the packed row layout from fill alone, sources = rows of an [E,G,C,M] buffer; clears zero_row
 int launch_row_maps_from_fill(const moe_config& c, const int32_t* fill, const RowPacking& pk,
                               void* zero_row, hipStream_t st);
@@ -150,7 +151,7 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 // both GEMMs over the packed row layout (bf16 layers the persistent kernel takes, M >= 128)
 bool expert_ffn_can_pack(const moe_config& c);
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
-                             const void* zero_row, const void* wi, const void* wo, void* h,
+                             const int32_t* fill, const void* zero_row, const void* wi, const void* wo, void* h,
                              void* out, bool scatter_out, hipStream_t st, void* event_between);
 inline size_t expert_signbits_bytes(const moe_config& c) {
   return (size_t)c.E * c.G * c.C * c.H / 8;

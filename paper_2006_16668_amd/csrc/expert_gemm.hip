@@ -268,9 +268,11 @@ struct DmaSmem {
 // in the tile's first K step; the waits of the next two steps cover them.
 // GATHER 2: the indices are absolute rows of the matrix A ([rows, K], row p of expert e comes
 // from row src_token[e * R + p], -1 = zero row): the packed row layout (RowPacking).
-// PACKED: expert e has only its first row_tile_start[e+1] - row_tile_start[e] row tiles multiplied
-// (the tiles of all experts are numbered consecutively in expert order; a block's tile numbers only
-// grow, so it finds a tile's expert by stepping a cursor forward).  SCATTER (with PACKED):
+// PACKED: expert e has only its first ceil(kept_e / 256) row tiles multiplied, kept_e = sum over g
+// of fill[g,e]: every block sums fill and forms the running tile counts in LDS when it starts;
+// the tiles of all experts are numbered consecutively in expert order, and since a block's tile
+// numbers only grow it finds a tile's expert by stepping a cursor forward.  Rows from kept_e to
+// the end of the last tile are multiplied as zero rows.  SCATTER (with PACKED):
 // the rows of C go to the absolute rows src_token[e * R + p] of Cout ([rows, N]), -1 = not stored.
 template <int ST, int EPI, int GATHER, bool A_MNC, bool B_KC, bool PACKED, bool SCATTER>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     int R, int N, int K, int tiles_m, int tiles_n, int ntiles_static,
     const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
     uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask,
-    unsigned char* __restrict__ signbits, const int32_t* __restrict__ row_tile_start, int E) {
+    unsigned char* __restrict__ signbits, const int32_t* __restrict__ fill, int E, int groups) {
   static_assert(!(GATHER && A_MNC), "the gather form addresses whole rows of a K-contiguous A");
   static_assert(!SCATTER || (PACKED && EPI == 0), "scattered rows: plain bf16 result of a packed launch");
   constexpr bool RELU = EPI == 1 || EPI == 4;
@@ -298,8 +300,44 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // about 8 row tiles x 4 column tiles, the split that shares the most operand panels in that
   // XCD's L2 (a tall output, as in the weight gradients, would otherwise re-read its A panel
   // once per column tile).
-  constexpr int kBand = 8;
-  const int ntiles = PACKED ? row_tile_start[E] * tiles_n : ntiles_static;   // uniform
+#ifndef MOE_DMA_KBAND
+#define MOE_DMA_KBAND 8
+#endif
+  constexpr int kBand = MOE_DMA_KBAND;
+  // PACKED: kept_s[e] = occupied rows of expert e, rts_s[e] = occupied row tiles of the experts
+  // before e (rts_s[E] = all of them), behind the stages and the token / bit areas in LDS
+  int* const kept_s = reinterpret_cast<int*>(smem_raw + SM::kBytes + (GATHER ? 1024 : 0) + (EPI == 5 ? 8192 : 0));
+  int* const rts_s = kept_s + E;
+  if (PACKED) {
+    for (int e = tid; e < E; e += 256) {
+      int k = 0;
+      for (int g = 0; g < groups; ++g) k += fill[(size_t)g * E + e];
+      kept_s[e] = k;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // lane l scans experts [l per, (l+1) per); the lanes' sums meet in a wavefront scan
+      const int per = (E + 63) / 64, b0 = lane * per;
+      int sum = 0;
+      for (int j = 0; j < per; ++j)
+        if (b0 + j < E) sum += (kept_s[b0 + j] + 255) >> 8;
+      int incl = sum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      int run = incl - sum;
+      for (int j = 0; j < per; ++j)
+        if (b0 + j < E) {
+          rts_s[b0 + j] = run;
+          run += (kept_s[b0 + j] + 255) >> 8;
+        }
+      if (lane == 63) rts_s[E] = incl;
+    }
+    __syncthreads();
+  }
+  const int ntiles = PACKED ? __builtin_amdgcn_readfirstlane(rts_s[E]) * tiles_n : ntiles_static;
   // PACKED: expert of the tile located last and its range of row tiles [rs, re) in the global
   // numbering; one cursor for the copies (producer side), one for the epilogues
   struct TileCursor { int e, rs, re; };
@@ -309,11 +347,11 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   {                                                                                          \
     int t_, tm_;                                                                             \
     if (PACKED) {                                                                            \
-      /* ends at the latest with e = E - 1: T_ < ntiles = row_tile_start[E] * tiles_n */     \
+      /* ends at the latest with e = E - 1: T_ < ntiles = rts_s[E] * tiles_n */              \
       while ((T_) >= CUR_.re * tiles_n && CUR_.e + 1 < E) {                                  \
         ++CUR_.e;                                                                            \
         CUR_.rs = CUR_.re;                                                                   \
-        CUR_.re = row_tile_start[CUR_.e + 1];                                                \
+        CUR_.re = __builtin_amdgcn_readfirstlane(rts_s[CUR_.e + 1]);                         \
       }                                                                                      \
       e_ = CUR_.e;                                                                           \
       t_ = (T_) - CUR_.rs * tiles_n;                                                         \
@@ -385,7 +423,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       const int ca_ = (lane & 3) ^ ((row_ >> 2) & 3);                                        \
       const bf16_t* src_;                                                                    \
       if (GATHER == 2) {                                                                     \
-        src_ = tok_ >= 0 ? A + (size_t)tok_ * K : zero_row;                                  \
+        src_ = (m0_) + row_ < kept_s[e_] && tok_ >= 0 ? A + (size_t)tok_ * K : zero_row;     \
       } else {                                                                               \
         const uint32_t n_ = (uint32_t)((m0_) + row_);                                        \
         const uint32_t g_ = c_magic ? __umulhi(n_, c_magic) >> c_shift : n_; /* n_ / C */    \
@@ -592,8 +630,10 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       int drow[8];                                             // SCATTER: destination rows
       if (SCATTER) {
 #pragma unroll
-        for (int ps = 0; ps < 8; ++ps)
-          drow[ps] = src_token[(size_t)e * R + m0 + wm0 + 32 * i + 4 * ps + (lane >> 4)];
+        for (int ps = 0; ps < 8; ++ps) {
+          const int pr = m0 + wm0 + 32 * i + 4 * ps + (lane >> 4);
+          drow[ps] = pr < kept_s[e] ? src_token[(size_t)e * R + pr] : -1;
+        }
       }
       u32x4_t mk[8];
       if (EPI == 2) {
@@ -669,10 +709,13 @@ template <int ST, int EPI, int GATHER, bool A_MNC = false, bool B_KC = false, bo
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
                     const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st,
                     const bf16_t* mask = nullptr, unsigned char* signbits = nullptr,
-                    const int32_t* row_tile_start = nullptr) {
+                    const int32_t* fill = nullptr, int G = 0) {
   using SM = DmaSmem<ST>;
   static_assert(!(GATHER && EPI == 5), "the two users of the spare LDS exclude each other");
-  constexpr size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0) + (EPI == 5 ? 8192 : 0);
+  // PACKED: 2 E + 1 more integers of LDS (row counts and running tile counts of the experts)
+  const size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0) + (EPI == 5 ? 8192 : 0) +
+                      (PACKED ? align_up(((size_t)2 * E + 1) * sizeof(int32_t), 16) : 0);
+  if (kLds > 160 * 1024) return MOE_EUNSUPPORTED;
   // n / C for n < 2^31 as (n * c_magic) >> (32 + c_shift), c_magic = ceil(2^(31+l) / C) with
   // l = ceil(log2 C); C == 1 is flagged by c_magic == 0
   uint32_t c_magic = 0;
@@ -683,7 +726,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
     c_magic = (uint32_t)((((unsigned long long)1 << (31 + l)) + C - 1) / C);
     c_shift = l - 1;
   }
-  if (PACKED && row_tile_start == nullptr) return MOE_EINVAL;
+  if (PACKED && fill == nullptr) return MOE_EINVAL;
   auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER>;
   // per device, once: the kernel's LDS limit and the number of compute units.  The cached
   // values are constants of the device, so a race between two first calls is harmless.
@@ -693,7 +736,8 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   if (cus_of[dev] == 0) {
     int n = 0;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess ||
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            PACKED ? 160 * 1024 : (int)kLds) != hipSuccess ||
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
       return MOE_EHIP;
     cus_of[dev] = n;
@@ -705,7 +749,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
                      tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask, signbits,
-                     row_tile_start, E);
+                     fill, E, G);
   return check_launch();
 }
 
@@ -830,14 +874,14 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 // h and (scatter_out == false) out hold packed rows; scatter_out sends the rows of out back to
 // the absolute rows pk.packed_src names.
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
-                             const void* zero_row, const void* wi, const void* wo, void* h,
+                             const int32_t* fill, const void* zero_row, const void* wi, const void* wo, void* h,
                              void* out, bool scatter_out, hipStream_t st, void* event_between) {
-  if (!expert_gemm1_can_gather(c) || !dma_shape_ok(c.G * c.C, c.M, c.H)) return MOE_EUNSUPPORTED;
+  if (!expert_ffn_can_pack(c)) return MOE_EUNSUPPORTED;
   const int R = c.G * c.C;
   int rc = launch_bf16_dma<4, 1, 2, false, false, true>(
       static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(h), c.E, R,
       c.H, c.M, pk.packed_src, static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr, nullptr,
-      pk.row_tile_start);
+      fill, c.G);
   if (rc != MOE_OK) return rc;
   if (event_between != nullptr &&
       hipEventRecord(static_cast<hipEvent_t>(event_between), st) != hipSuccess)
@@ -845,14 +889,15 @@ int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPackin
   if (scatter_out)
     return launch_bf16_dma<4, 0, 0, false, false, true, true>(
         static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E,
-        R, c.M, c.H, pk.packed_src, nullptr, 0, 0, st, nullptr, nullptr, pk.row_tile_start);
+        R, c.M, c.H, pk.packed_src, nullptr, 0, 0, st, nullptr, nullptr, fill, c.G);
   return launch_bf16_dma<4, 0, 0, false, false, true, false>(
       static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E, R,
-      c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, pk.row_tile_start);
+      c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, fill, c.G);
 }
 
 bool expert_ffn_can_pack(const moe_config& c) {
-  return expert_gemm1_can_gather(c) && dma_shape_ok(c.G * c.C, c.M, c.H);
+  // E: the kernels keep 2 E + 1 integers in the LDS left over by the stages
+  return expert_gemm1_can_gather(c) && dma_shape_ok(c.G * c.C, c.M, c.H) && c.E <= 2048;
 }
 
 int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void* out,

@@ -222,7 +222,7 @@ __device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
 // chunk whose logits sit in LDS (zs, row pitch `pitch` floats).  NT threads:
 // TPT = NT/64 per token, expert e handled by thread e % TPT of the token's group.
 // Must be called by all threads of the block; ends with a barrier.
-template <int NT>
+template <int NT, int EMAX>
 __device__ __forceinline__ void gate_chunk_epilogue(
     float* zs, int pitch, int g, int ch, int S, int E, int nch, const float* __restrict__ u,
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
@@ -230,6 +230,7 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     float* __restrict__ msum, int* h1, int* h2) {
   constexpr int TPT = NT / 64;
   __shared__ float rinv[kChunk];
+  __shared__ float mpart[8 * EMAX];
   const int tid = threadIdx.x;
   for (int e = tid; e < E; e += NT) { h1[e] = 0; h2[e] = 0; }
   __syncthreads();
@@ -281,17 +282,25 @@ __device__ __forceinline__ void gate_chunk_epilogue(
   }
   __syncthreads();
   const size_t base = ((size_t)g * nch + ch) * E;
+  // Gate sums of the chunk in a fixed order: eight interleaved partial sums over the 64 rows
+  // (partial q takes rows q, q + 8, ...; rows past the end of the group carry rinv = 0), then a
+  // tree.  tpe = 8, 4, 2 or 1 threads share the partial sums of one expert.
+  int tpe = 8;
+  while (tpe * E > NT) tpe >>= 1;
+  {
+    const int e = tid / tpe, j = tid - e * tpe;
+    if (e < E)
+      for (int q = j; q < 8; q += tpe) {
+        float part = 0.f;
+#pragma unroll
+        for (int r0 = 0; r0 < kChunk; r0 += 8) part = fmaf(zs[(size_t)(r0 + q) * pitch + e], rinv[r0 + q], part);
+        mpart[8 * e + q] = part;
+      }
+  }
+  __syncthreads();
   for (int e = tid; e < E; e += NT) {
-    // fixed summation order: eight interleaved partial sums over the 64 rows, then a tree
-    // (rows past the end of the group carry rinv = 0)
-    float part[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) part[q] = 0.f;
-#pragma unroll
-    for (int r0 = 0; r0 < kChunk; r0 += 8)
-#pragma unroll
-      for (int q = 0; q < 8; ++q) part[q] = fmaf(zs[(size_t)(r0 + q) * pitch + e], rinv[r0 + q], part[q]);
-    msum[base + e] = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+    const float* pp = mpart + 8 * e;
+    msum[base + e] = ((pp[0] + pp[1]) + (pp[2] + pp[3])) + ((pp[4] + pp[5]) + (pp[6] + pp[7]));
     hist1[base + e] = h1[e];
     hist2[base + e] = h2[e];
   }
@@ -410,7 +419,7 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
   for (int c = 0; c < 2; ++c) {
     const int ch = 2 * pr + c;
     if (ch < nch)                                     // block-uniform
-      gate_chunk_epilogue<256>(part + (size_t)c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx,
+      gate_chunk_epilogue<256, Epad>(part + (size_t)c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx,
                                slot, weight, gates_opt, hist1, hist2, msum, hh, hh + Epad);
   }
 }
@@ -538,7 +547,7 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
           zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
               c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
     __syncthreads();
-    gate_chunk_epilogue<NT>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+    gate_chunk_epilogue<NT, Epad>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
                             hist1, hist2, msum, hh, hh + Epad);
   }
 }
@@ -682,7 +691,7 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
                 c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
     }
     __syncthreads();
-    gate_chunk_epilogue<NT>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+    gate_chunk_epilogue<NT, Epad>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
                             hist1, hist2, msum, hh, hh + Epad);
   }
 }
@@ -752,42 +761,6 @@ __device__ __forceinline__ int wave_sum_int(int v) {
   return v;
 }
 
-// Book-keeping of the packed row layout (see RowPacking), shared by the two kernels that build
-// the maps; called by one wavefront per block, b = block index of nb blocks:
-//   - the rows between an expert's last kept row and the end of its last 256-row tile get the
-//     source -1 (they are multiplied as zero rows and never read back);
-//   - block 0 writes the running count of occupied 256-row tiles over the experts,
-//     row_tile_start[e] = sum over e' < e of ceil(kept_e' / 256), and the total at index E.
-__device__ __forceinline__ void pack_bookkeeping(int b, int nb, int lane, int G, int E, int R,
-                                                 const int32_t* __restrict__ fill, const RowPacking& pk) {
-  for (int e = b; e < E; e += nb) {
-    int kept = 0;
-    for (int g = lane; g < G; g += 64) kept += fill[(size_t)g * E + e];
-    kept = wave_sum_int(kept);
-    const int end = (kept + 255) / 256 * 256;          // <= R: kept <= R and R % 256 == 0
-    for (int p = kept + lane; p < end; p += 64) pk.packed_src[(size_t)e * R + p] = -1;
-  }
-  if (b == 0) {
-    int run = 0;
-    for (int e0 = 0; e0 < E; e0 += 64) {
-      const int e = e0 + lane;
-      int kept = 0;
-      if (e < E)
-        for (int g = 0; g < G; ++g) kept += fill[(size_t)g * E + e];
-      const int nt = (kept + 255) / 256;
-      int incl = nt;                                     // inclusive scan over the lanes
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const int v = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += v;
-      }
-      if (e < E) pk.row_tile_start[e] = run + incl - nt;
-      run += __shfl(incl, 63, 64);
-    }
-    if (lane == 0) pk.row_tile_start[E] = run;
-  }
-}
-
 // One wavefront per chunk.  pk.packed_src != NULL: also builds the packed row layout of the
 // expert GEMMs (row of a kept choice = kept rows of the same expert in earlier groups + slot).
 __global__ __launch_bounds__(64) void gate_slots_kernel(
@@ -811,14 +784,17 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
       part += ((float)c1[(size_t)g * E + e] / (float)S) * mean_gate[(size_t)g * E + e];
     part = wave_sum(part);
     if (lane == 0) aux[g] = part / (float)E;
-    if (packing)
-      for (int e = lane; e < E; e += 64) {
-        int rb = 0;
-        for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
-        pk.row_base[(size_t)g * E + e] = rb;
-      }
   }
-  if (packing) pack_bookkeeping(blockIdx.x, gridDim.x, lane, G, E, G * C, fill, pk);
+  // packed layout: row_base[:, e] = running sum of fill[:, e] over the groups, 64 experts per
+  // block (coalesced rows of fill, G loads per lane)
+  if (packing)
+    for (int e = 64 * blockIdx.x + lane; e < E; e += 64 * gridDim.x) {   // no wave-level ops inside
+      int run = 0;
+      for (int gg = 0; gg < G; ++gg) {
+        pk.row_base[(size_t)gg * E + e] = run;
+        run += fill[(size_t)gg * E + e];
+      }
+    }
   const int s = ch * kChunk + lane;
   const bool valid = s < S;
   const size_t n = (size_t)g * S + (valid ? s : 0);
@@ -829,6 +805,22 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
     sampled = slot[2 * n + 1] != MOE_SLOT_NOT_SAMPLED;
     if (sampled) e2 = expert_idx[2 * n + 1];
   }
+  // packed layout: kept rows of the two experts in the groups before this one (loads that the
+  // rank loop below hides)
+  // Up to 128 experts: lane l sums the columns l and l + 64 of fill (coalesced) and the sums
+  // meet in LDS after the rank loop; wider gates: every lane sums the columns of its own two
+  // experts.
+  __shared__ int rb_s[128];
+  const bool rb_shared = E <= 128;
+  int rb1 = 0, rb2 = 0;
+  if (packing) {
+    const int ca = rb_shared ? (lane < E ? lane : -1) : e1;
+    const int cb = rb_shared ? (lane + 64 < E ? lane + 64 : -1) : e2;
+    for (int gg = 0; gg < g; ++gg) {
+      if (ca >= 0) rb1 += fill[(size_t)gg * E + ca];
+      if (cb >= 0) rb2 += fill[(size_t)gg * E + cb];
+    }
+  }
   int r1 = 0, r2 = 0;
   for (int i = 0; i < kChunk - 1; ++i) {
     const int o1 = __shfl(e1, i, 64);
@@ -837,6 +829,13 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
       r1 += (o1 == e1);
       r2 += (o2 == e2);
     }
+  }
+  if (packing && rb_shared) {
+    rb_s[lane] = rb1;
+    rb_s[lane + 64] = rb2;
+    __syncthreads();                                  // the block is this one wavefront
+    rb1 = e1 >= 0 ? rb_s[e1] : 0;
+    rb2 = e2 >= 0 ? rb_s[e2] : 0;
   }
   if (!valid) return;
   const size_t cb = ((size_t)g * nch + ch) * E;
@@ -855,11 +854,6 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
   if (s2 >= 0) src_token[((size_t)e2 * G + g) * C + s2] = s;
   if (packing) {
     const size_t R = (size_t)G * C;
-    int rb1 = 0, rb2 = 0;
-    for (int gg = 0; gg < g; ++gg) {
-      if (s1 >= 0) rb1 += fill[(size_t)gg * E + e1];
-      if (s2 >= 0) rb2 += fill[(size_t)gg * E + e2];
-    }
     if (s1 >= 0) pk.packed_src[(size_t)e1 * R + rb1 + s1] = (int32_t)n;
     if (s2 >= 0) pk.packed_src[(size_t)e2 * R + rb2 + s2] = (int32_t)n;
   }
@@ -874,19 +868,13 @@ __global__ __launch_bounds__(64) void row_maps_from_fill_kernel(
   if (blockIdx.x == 0)
     for (int i = lane; i < zero_words; i += 64) zero_fill[i] = 0u;
   const size_t R = (size_t)G * C;
-  pack_bookkeeping(blockIdx.x, gridDim.x, lane, G, E, (int)R, fill, pk);
   const long long idx = (long long)blockIdx.x * 64 + lane;
   if (idx >= (long long)E * G * C) return;
   const int c = (int)(idx % C), g = (int)((idx / C) % G), e = (int)(idx / ((long long)C * G));
-  if (c == 0) {
-    int rb = 0;
-    for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
-    pk.row_base[(size_t)g * E + e] = rb;
-  }
-  if (c >= fill[(size_t)g * E + e]) return;
   int rb = 0;
   for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
-  pk.packed_src[(size_t)e * R + rb + c] = (int32_t)idx;
+  if (c == 0) pk.row_base[(size_t)g * E + e] = rb;
+  if (c < fill[(size_t)g * E + e]) pk.packed_src[(size_t)e * R + rb + c] = (int32_t)idx;
 }
 
 template <typename T, bool PRE = false>
@@ -996,32 +984,57 @@ size_t gate_workspace_bytes(const moe_config& c) {
          align_up(w.w_bytes, 256) + align_up(w.z_bytes, 256) + align_up(w.x_bytes, 256);
 }
 
+// The gate weights in the form the logit kernels multiply: three bf16 terms per weight in the
+// MFMA operand order (E <= 512, bf16 activations) or as the K-contiguous operand of the logit
+// GEMM (wider gates, fp32 activations with GEMM-friendly shapes); 0 bytes when the gate reads
+// wg as it is.
+size_t gate_pack_bytes(const moe_config& c) {
+  const PackGeom pg = pack_geom(c);
+  return pg.bytes != 0 ? pg.bytes : wide_geom(c).w_bytes;
+}
+
+int launch_gate_pack(const moe_config& c, const float* wg, void* packed, hipStream_t st) {
+  const WideGeom w = wide_geom(c);
+  if (w.cols != 0) {
+    const long long n = (long long)w.cols * w.k;
+    hipLaunchKernelGGL(gate_pack_wide_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
+                       static_cast<bf16_t*>(packed), c.M, c.E, w.cols, w.k / c.M);
+    return check_launch();
+  }
+  const PackGeom pg = pack_geom(c);
+  if (pg.bytes == 0) return MOE_OK;
+  const int total = pg.KS * pg.T * 64;
+  hipLaunchKernelGGL(gate_pack_wg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, wg,
+                     static_cast<uint4*>(packed), c.M, c.E, pg.T, total);
+  return check_launch();
+}
+
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
                 float* gates_opt, void* ws, void* zero_row, const RowPacking* packing,
-                hipStream_t st) {
+                const void* wg_prepacked, hipStream_t st) {
   const int nch = (c.S + kChunk - 1) / kChunk;
   const size_t seg = align_up((size_t)c.G * nch * c.E * 4, 256);
   int32_t* hist1 = reinterpret_cast<int32_t*>(ws);
   int32_t* hist2 = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + seg);
   float* msum = reinterpret_cast<float*>(static_cast<char*>(ws) + 2 * seg);
-  uint4* wgP = reinterpret_cast<uint4*>(static_cast<char*>(ws) + 3 * seg);
+  // the packed weights: the caller's (packed once with launch_gate_pack) or this call's own
+  char* const own = static_cast<char*>(ws) + 3 * seg;
+  uint4* wgP = wg_prepacked != nullptr ? static_cast<uint4*>(const_cast<void*>(wg_prepacked))
+                                        : reinterpret_cast<uint4*>(own);
   const PackGeom pg = pack_geom(c);
   int rc;
+  if (wg_prepacked == nullptr && (rc = launch_gate_pack(c, wg, own, st)) != MOE_OK) return rc;
   if (wide_geom(c).cols != 0) {
     // pg.bytes == 0 here: the packed-operand region is empty; wgk, the logits and (fp32) the
     // split activations follow it
     const WideGeom w = wide_geom(c);
     const long long tokens = (long long)c.G * c.S;
-    bf16_t* wgk = reinterpret_cast<bf16_t*>(wgP);
-    char* after = reinterpret_cast<char*>(wgP) + align_up(w.w_bytes, 256);
+    const bf16_t* wgk = reinterpret_cast<const bf16_t*>(wgP);
+    char* after = own + align_up(w.w_bytes, 256);
     float* zpre = reinterpret_cast<float*>(after);
     bf16_t* xk = reinterpret_cast<bf16_t*>(after + align_up(w.z_bytes, 256));
-    const long long n = (long long)w.cols * w.k;
-    hipLaunchKernelGGL(gate_pack_wide_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wg,
-                       wgk, c.M, c.E, w.cols, w.k / c.M);
-    if ((rc = check_launch()) != MOE_OK) return rc;
     const void* a = x;
     if (c.act_dtype == MOE_F32) {
       hipLaunchKernelGGL(gate_split_x_kernel, dim3((unsigned)((tokens * c.M + 255) / 256)), dim3(256),
@@ -1043,10 +1056,6 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
     rc = launch_topk<bf16_t>(c, nch, static_cast<const bf16_t*>(x), wg, u, expert_idx, slot,
                              weight, gates_opt, hist1, hist2, msum, st);
   } else {
-    const int total = pg.KS * pg.T * 64;
-    hipLaunchKernelGGL(gate_pack_wg_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       wg, wgP, c.M, c.E, pg.T, total);
-    if ((rc = check_launch()) != MOE_OK) return rc;
     const dim3 grid((unsigned)(c.G * ((nch + 1) / 2))), block(256);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
@@ -1080,7 +1089,7 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
                      c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token, c1,
                      mean_gate, aux, static_cast<uint32_t*>(zero_row),
                      zero_row != nullptr ? c.M / 2 : 0, fill,
-                     packing != nullptr ? *packing : RowPacking{nullptr, nullptr, nullptr});
+                     packing != nullptr ? *packing : RowPacking{nullptr, nullptr});
   return check_launch();
 }
 

@@ -128,6 +128,25 @@ def test_stages_and_layer_match_oracle(cfg):
     assert torch.equal(y2, y)
     assert torch.equal(aux2, r["aux"])
 
+    # --- gate weights packed once by the caller (moe_gate_pack): same bits from both entry points
+    nbytes = moe.moe_gate_pack_bytes(sh)
+    wgp = torch.empty(nbytes, dtype=torch.uint8, device=DEV) if nbytes else None
+    moe.moe_gate_pack(sh, inp.wg, wgp)
+    y3 = torch.full_like(y, float("nan"))
+    aux3 = torch.full_like(aux2, float("nan"))
+    lws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    moe.moe_forward_prepacked(sh, inp.x, inp.wg, wgp, inp.u, inp.wi, inp.wo, y3, aux3, lws)
+    torch.cuda.synchronize()
+    assert torch.equal(y3, y) and torch.equal(aux3, r["aux"])
+    r3 = {k: torch.full_like(v, -9) for k, v in r.items() if v is not None}
+    gws = torch.empty(moe.moe_gate_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    moe.moe_gate_prepacked(sh, inp.x, inp.wg, wgp, inp.u, r3["expert_idx"], r3["slot"], r3["weight"],
+                           r3["fill"], r3["src_token"], r3["c1"], r3["mean_gate"], r3["aux"],
+                           r3["gates"], gws)
+    torch.cuda.synchronize()
+    for k in r3:
+        assert torch.equal(r3[k], r[k]), k
+
     # --- experts again with fill and a workspace: occupied rows only.  Same bits in every
     # occupied slot; where the kernels pack (moe_forward_packs_rows) the other slots of out are
     # not written, elsewhere the call is the one above
