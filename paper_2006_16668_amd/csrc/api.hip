@@ -148,8 +148,7 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
   if (packed) {
-    rc = moe::launch_expert_ffn_packed(*cfg, x, pk, reinterpret_cast<const int32_t*>(base + w.fill),
-                                       base + w.zero_row, wi, wo, base + w.h,
+    rc = moe::launch_expert_ffn_packed(*cfg, x, pk, base + w.zero_row, wi, wo, base + w.h,
                                        base + w.out, false, st, events != nullptr ? events[3] : nullptr);
     if (rc != MOE_OK) return rc;
   } else {
@@ -499,8 +498,7 @@ int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, 
     void* zero_row = static_cast<char*>(ws) + maps;
     int r = moe::launch_row_maps_from_fill(*cfg, fill, pk, zero_row, st);
     if (r != MOE_OK) return r;
-    return moe::launch_expert_ffn_packed(*cfg, buf, pk, fill, zero_row, wi, wo, h_ws, out, true, st,
-                                         nullptr);
+    return moe::launch_expert_ffn_packed(*cfg, buf, pk, zero_row, wi, wo, h_ws, out, true, st, nullptr);
   }
   const int rc1 = moe::launch_expert_gemm1(*cfg, buf, wi, h_ws, st);
   if (rc1 != MOE_OK) return rc1;

@@ -91,15 +91,16 @@ __device__ __forceinline__ float wave_sum(float v) {
 // a token or nothing, and FFN_e(0) = 0, so positions that hold nothing need not be multiplied).
 // The kept rows of expert e (kept_e = sum over g of fill[g,e]), in (group, slot) order, occupy
 // rows 0 .. kept_e - 1 of its block of R = G*C rows; only the ceil(kept_e / 256) row tiles that
-// hold them are multiplied.  The GEMM kernels derive kept_e and the tile counts from fill.
+// hold them are multiplied.  The GEMM kernels derive the tile counts from kept.
 struct RowPacking {
   int32_t* row_base;     // [G,E]  kept rows of expert e in the groups before g
+  int32_t* kept;         // [E]    kept_e
   int32_t* packed_src;   // [E,R]  source row of packed row p < kept_e (a row index into the A
                          //        operand's matrix); entries from kept_e on are not written
 };
-inline size_t row_packing_bytes(const moe_config& c) {      // both arrays, each 256-aligned
+inline size_t row_packing_bytes(const moe_config& c) {      // the three arrays, each 256-aligned
   const size_t rows = (size_t)c.E * c.G * c.C;
-  return align_up((size_t)c.G * c.E * 4, 256) + align_up(rows * 4, 256);
+  return align_up((size_t)c.G * c.E * 4, 256) + align_up((size_t)c.E * 4, 256) + align_up(rows * 4, 256);
 }
 inline RowPacking carve_row_packing(const moe_config& c, void* base) {
   const size_t rows = (size_t)c.E * c.G * c.C;
@@ -107,6 +108,8 @@ inline RowPacking carve_row_packing(const moe_config& c, void* base) {
   RowPacking pk;
   pk.row_base = reinterpret_cast<int32_t*>(p);
   p += align_up((size_t)c.G * c.E * 4, 256);
+  pk.kept = reinterpret_cast<int32_t*>(p);
+  p += align_up((size_t)c.E * 4, 256);
   pk.packed_src = reinterpret_cast<int32_t*>(p);
   (void)rows;
   return pk;
@@ -151,7 +154,7 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 // both GEMMs over the packed row layout (bf16 layers the persistent kernel takes, M >= 128)
 bool expert_ffn_can_pack(const moe_config& c);
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
-                             const int32_t* fill, const void* zero_row, const void* wi, const void* wo, void* h,
+                             const void* zero_row, const void* wi, const void* wo, void* h,
                              void* out, bool scatter_out, hipStream_t st, void* event_between);
 inline size_t expert_signbits_bytes(const moe_config& c) {
   return (size_t)c.E * c.G * c.C * c.H / 8;

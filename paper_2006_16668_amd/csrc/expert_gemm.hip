@@ -268,21 +268,24 @@ struct DmaSmem {
 // in the tile's first K step; the waits of the next two steps cover them.
 // GATHER 2: the indices are absolute rows of the matrix A ([rows, K], row p of expert e comes
 // from row src_token[e * R + p], -1 = zero row): the packed row layout (RowPacking).
-// PACKED: expert e has only its first ceil(kept_e / 256) row tiles multiplied, kept_e = sum over g
-// of fill[g,e]: every block sums fill and forms the running tile counts in LDS when it starts;
-// the tiles of all experts are numbered consecutively in expert order, and since a block's tile
-// numbers only grow it finds a tile's expert by stepping a cursor forward.  Rows from kept_e to
-// the end of the last tile are multiplied as zero rows.  SCATTER (with PACKED):
+// PACKED: expert e has only its first ceil(kept[e] / 256) row tiles multiplied (kept[e] = its
+// occupied rows): every block copies kept to LDS and forms the running tile counts there when it
+// starts; the tiles of all experts are numbered consecutively in expert order, and since a
+// block's tile numbers only grow it finds a tile's expert by stepping a cursor forward.  Rows
+// from kept[e] to the end of the last tile are multiplied as zero rows.  SCATTER (with PACKED):
 // the rows of C go to the absolute rows src_token[e * R + p] of Cout ([rows, N]), -1 = not stored.
-template <int ST, int EPI, int GATHER, bool A_MNC, bool B_KC, bool PACKED, bool SCATTER>
+// DYNK: the sum over k of expert e stops at 256 ceil(kept[e] / 256) instead of K (the weight
+// gradients, whose k runs over an expert's packed rows); an expert with no rows gets zeros.
+template <int ST, int EPI, int GATHER, bool A_MNC, bool B_KC, bool PACKED, bool SCATTER, bool DYNK>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
     int R, int N, int K, int tiles_m, int tiles_n, int ntiles_static,
     const int32_t* __restrict__ src_token, const bf16_t* __restrict__ zero_row, int S,
     uint32_t c_magic, int c_shift, const bf16_t* __restrict__ mask,
-    unsigned char* __restrict__ signbits, const int32_t* __restrict__ fill, int E, int groups) {
+    unsigned char* __restrict__ signbits, const int32_t* __restrict__ kept, int E) {
   static_assert(!(GATHER && A_MNC), "the gather form addresses whole rows of a K-contiguous A");
   static_assert(!SCATTER || (PACKED && EPI == 0), "scattered rows: plain bf16 result of a packed launch");
+  static_assert(!(DYNK && (PACKED || GATHER)), "a shortened k range comes with the full list of output tiles");
   constexpr bool RELU = EPI == 1 || EPI == 4;
   using SM = DmaSmem<ST>;
   constexpr int BM = 256, BN = 256, BK = 32, TM = 4, TN = 4;
@@ -308,13 +311,11 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // before e (rts_s[E] = all of them), behind the stages and the token / bit areas in LDS
   int* const kept_s = reinterpret_cast<int*>(smem_raw + SM::kBytes + (GATHER ? 1024 : 0) + (EPI == 5 ? 8192 : 0));
   int* const rts_s = kept_s + E;
-  if (PACKED) {
-    for (int e = tid; e < E; e += 256) {
-      int k = 0;
-      for (int g = 0; g < groups; ++g) k += fill[(size_t)g * E + e];
-      kept_s[e] = k;
-    }
+  if (PACKED || DYNK) {
+    for (int e = tid; e < E; e += 256) kept_s[e] = kept[e];
     __syncthreads();
+  }
+  if (PACKED) {
     if (wave == 0) {
       // lane l scans experts [l per, (l+1) per); the lanes' sums meet in a wavefront scan
       const int per = (E + 63) / 64, b0 = lane * per;
@@ -377,9 +378,9 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   const int t_end = t_begin + xq + (xcd < xr ? 1 : 0);
   const int stride = (nb - xcd + kXcds - 1) / kXcds;           // blocks on this XCD
   const int first = t_begin + slot;
-  const int my_tiles = first < t_end ? (t_end - first + stride - 1) / stride : 0;
-  const int G = my_tiles * KT;                                 // K steps of this block
-  if (G == 0) return;                                          // block-uniform
+  if (first >= t_end) return;                                  // block-uniform
+  // K steps of a tile of expert e_
+#define MOE_DMA_STEPS(e_) (DYNK ? ((kept_s[e_] + 255) >> 8) * (256 / BK) : KT)
 
   // per-lane source byte offsets of the 4 + 4 copy instructions of this wavefront
   uint32_t a_voff[4], b_voff[4];
@@ -394,7 +395,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   }
 
   // producer cursor: the next step to copy (tile p_tile, k step p_kt) and its sources
-  int p_tile = first, p_kt = 0, p_stage = 0, p_g = 0;
+  // (p_steps: steps of that tile; p_more: such a step exists; p_g: steps started so far)
+  int p_tile = first, p_kt = 0, p_stage = 0, p_g = 0, p_steps = KT, p_more = 1;
   const bf16_t* p_a;
   const bf16_t* p_b;
   // GATHER: per-lane source addresses of the 4 row copies.  The 64 dispatch indices of this
@@ -439,12 +441,19 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   if (GATHER) { MOE_DMA16_ADDR(LDS_U32, a_addr[q]); } else { MOE_DMA16(LDS_U32, a_voff[q], p_a); }
 #define MOE_DMA_SET_SOURCES()                                                                \
   {                                                                                          \
-    MOE_DMA_TILE(p_tile, pcur, e_, rt_, ct_)                                                 \
-    if (GATHER) MOE_DMA_GATHER_ROWS(e_, rt_ * BM)                                            \
-    else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)rt_ * BM;                         \
-    else p_a = A + ((size_t)e_ * R + (size_t)rt_ * BM) * K;                                  \
-    if (B_KC) p_b = B + ((size_t)e_ * N + (size_t)ct_ * BN) * K;                             \
-    else p_b = B + (size_t)e_ * K * N + (size_t)ct_ * BN;                                    \
+    if (DYNK) {                                 /* pass over tiles without a single k step */ \
+      while (p_tile < t_end && MOE_DMA_STEPS(p_tile / per_e) == 0) p_tile += stride;         \
+    }                                                                                        \
+    p_more = __builtin_amdgcn_readfirstlane(p_tile < t_end);                                 \
+    if (p_more) {                                                                            \
+      MOE_DMA_TILE(p_tile, pcur, e_, rt_, ct_)                                               \
+      p_steps = __builtin_amdgcn_readfirstlane(MOE_DMA_STEPS(e_));                           \
+      if (GATHER) MOE_DMA_GATHER_ROWS(e_, rt_ * BM)                                          \
+      else if (A_MNC) p_a = A + (size_t)e_ * K * R + (size_t)rt_ * BM;                       \
+      else p_a = A + ((size_t)e_ * R + (size_t)rt_ * BM) * K;                                \
+      if (B_KC) p_b = B + ((size_t)e_ * N + (size_t)ct_ * BN) * K;                           \
+      else p_b = B + (size_t)e_ * K * N + (size_t)ct_ * BN;                                  \
+    }                                                                                        \
   }
 #define MOE_DMA_ADVANCE()                                                                    \
   {                                                                                          \
@@ -455,7 +464,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       if (p_kt == KT - 4 && p_tile + stride < t_end) MOE_DMA_TOKENS(p_tile + stride)         \
     } else p_a += A_MNC ? (size_t)BK * R : (size_t)BK;                                       \
     p_b += B_KC ? (size_t)BK : (size_t)BK * N;                                               \
-    if (++p_kt == KT) { p_kt = 0; p_tile += stride; if (p_g < G) MOE_DMA_SET_SOURCES() }     \
+    if (++p_kt == p_steps) { p_kt = 0; p_tile += stride; MOE_DMA_SET_SOURCES() }             \
   }
   if (GATHER) {
     MOE_DMA_TOKENS(first)
@@ -506,9 +515,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((F).b[j], (F).a[i], acc[i][j], 0, 0, 0);
 
   Frags fr[2];
-  // start the first ST-1 steps, wait for step 0
-  const int pro = ST - 1 < G ? ST - 1 : G;
-  for (int tl = 0; tl < pro; ++tl) {
+  // start the first ST-1 steps (as many as there are), wait for step 0
+  for (int tl = 0; tl < ST - 1 && p_more; ++tl) {
     const uint32_t la_ = lds0 + p_stage * SM::kStage + wave * 4096;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -517,8 +525,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
     MOE_DMA_ADVANCE()
   }
-  if (pro >= 3) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else if (pro == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  if (p_g >= 3) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (p_g == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 #pragma unroll
@@ -529,6 +537,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // multiplies, from a valid stage): a conditional read would make every later wait
   // for LDS data wait for all outstanding reads instead of the older ones only.
   for (int c_tile = first; c_tile < t_end; c_tile += stride) {
+    MOE_DMA_TILE(c_tile, ccur, e, rt, ct)
+    const int c_steps = __builtin_amdgcn_readfirstlane(MOE_DMA_STEPS(e));
     f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -537,7 +547,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    for (int kt = 0; kt < KT; ++kt, ++g) {
+    for (int kt = 0; kt < c_steps; ++kt, ++g) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) { MOE_DMA_READ_A(fr[1], stage, 1, i) MOE_DMA_READ_B(fr[1], stage, 1, i) }
 #pragma unroll
@@ -552,7 +562,8 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       // (The counts pass through an empty asm so that the optimiser cannot peel or
       // duplicate the loop body around these conditions: copies of the body would shuffle
       // the 256 accumulator registers between them.)
-      int younger = p_g - 1 - (g + 1 < G ? g + 1 : G - 1);
+      // the step to await is g+1, or the last one when the producer has started them all
+      int younger = p_g - 1 - (p_more || g + 1 < p_g ? g + 1 : p_g - 1);
       if (kt < 2 && c_tile != first) younger = 3;              // landed before the last epilogue
       younger = __builtin_amdgcn_readfirstlane(younger);
       asm volatile("" : "+s"(younger));
@@ -561,14 +572,13 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
       else if (younger == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       __syncthreads();
       if (EPI == 5 && kt == 0) {
-        MOE_DMA_TILE(c_tile, ccur, e5, rt5, ct5)
-        const unsigned char* src5 = signbits + ((size_t)(e5 * tiles_m + rt5) * tiles_n + ct5) * 8192 +
+        const unsigned char* src5 = signbits + ((size_t)(e * tiles_m + rt) * tiles_n + ct) * 8192 +
                                     wave * 2048 + lane * 16;
         MOE_DMA16_ADDR(lds_bits, (uint64_t)(uintptr_t)src5);
         MOE_DMA16_ADDR(lds_bits + 1024, (uint64_t)(uintptr_t)(src5 + 1024));
       }
       const int nstage = stage + 1 == ST ? 0 : stage + 1;      // stage of step g+1
-      int more = __builtin_amdgcn_readfirstlane(p_g < G);      // p_stage: stage of step g-1, free now
+      int more = p_more;                                       // p_stage: stage of step g-1, free now
       asm volatile("" : "+s"(more));
       const uint32_t la_ = lds0 + p_stage * SM::kStage + wave * 4096;
       __builtin_amdgcn_sched_barrier(0);
@@ -594,7 +604,6 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     // row r at position c ^ (r & 15), its two 8-byte halves swapped when r >= 16 (then the
     // 32 lanes of a half-wave write 256 distinct bytes: no bank conflict).
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // every copy issued so far
-    MOE_DMA_TILE(c_tile, ccur, e, rt, ct)
     const int m0 = rt * BM, n0 = ct * BN;
     const size_t c_off = ((size_t)e * R + m0 + wm0) * N + n0 + wn0;
     bf16_t* Ce = Cout + c_off;
@@ -691,6 +700,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
     }
   }
 #undef MOE_DMA_SET_SOURCES
+#undef MOE_DMA_STEPS
 #undef MOE_DMA_TILE
 #undef MOE_DMA_GATHER_ROWS
 #undef MOE_DMA_TOKENS
@@ -705,16 +715,16 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 }
 
 template <int ST, int EPI, int GATHER, bool A_MNC = false, bool B_KC = false, bool PACKED = false,
-          bool SCATTER = false>
+          bool SCATTER = false, bool DYNK = false>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
                     const int32_t* src_token, const bf16_t* zero_row, int S, int C, hipStream_t st,
                     const bf16_t* mask = nullptr, unsigned char* signbits = nullptr,
-                    const int32_t* fill = nullptr, int G = 0) {
+                    const int32_t* kept = nullptr) {
   using SM = DmaSmem<ST>;
   static_assert(!(GATHER && EPI == 5), "the two users of the spare LDS exclude each other");
-  // PACKED: 2 E + 1 more integers of LDS (row counts and running tile counts of the experts)
+  // PACKED / DYNK: 2 E + 1 more integers of LDS (row counts and running tile counts of the experts)
   const size_t kLds = SM::kBytes + (GATHER ? 4 * 64 * sizeof(int32_t) : 0) + (EPI == 5 ? 8192 : 0) +
-                      (PACKED ? align_up(((size_t)2 * E + 1) * sizeof(int32_t), 16) : 0);
+                      (PACKED || DYNK ? align_up(((size_t)2 * E + 1) * sizeof(int32_t), 16) : 0);
   if (kLds > 160 * 1024) return MOE_EUNSUPPORTED;
   // n / C for n < 2^31 as (n * c_magic) >> (32 + c_shift), c_magic = ceil(2^(31+l) / C) with
   // l = ceil(log2 C); C == 1 is flagged by c_magic == 0
@@ -726,8 +736,8 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
     c_magic = (uint32_t)((((unsigned long long)1 << (31 + l)) + C - 1) / C);
     c_shift = l - 1;
   }
-  if (PACKED && fill == nullptr) return MOE_EINVAL;
-  auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER>;
+  if ((PACKED || DYNK) && kept == nullptr) return MOE_EINVAL;
+  auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER, DYNK>;
   // per device, once: the kernel's LDS limit and the number of compute units.  The cached
   // values are constants of the device, so a race between two first calls is harmless.
   static int cus_of[kMaxDevices] = {};
@@ -737,7 +747,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
     int n = 0;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                            PACKED ? 160 * 1024 : (int)kLds) != hipSuccess ||
+                            PACKED || DYNK ? 160 * 1024 : (int)kLds) != hipSuccess ||
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
       return MOE_EHIP;
     cus_of[dev] = n;
@@ -749,7 +759,7 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);   // one block per CU (LDS-bound)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), kLds, st, A, B, Cout, R, N, K, tiles_m,
                      tiles_n, (int)ntiles, src_token, zero_row, S, c_magic, c_shift, mask, signbits,
-                     fill, E, G);
+                     kept, E);
   return check_launch();
 }
 
@@ -874,14 +884,14 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 // h and (scatter_out == false) out hold packed rows; scatter_out sends the rows of out back to
 // the absolute rows pk.packed_src names.
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
-                             const int32_t* fill, const void* zero_row, const void* wi, const void* wo, void* h,
+                             const void* zero_row, const void* wi, const void* wo, void* h,
                              void* out, bool scatter_out, hipStream_t st, void* event_between) {
   if (!expert_ffn_can_pack(c)) return MOE_EUNSUPPORTED;
   const int R = c.G * c.C;
   int rc = launch_bf16_dma<4, 1, 2, false, false, true>(
       static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(h), c.E, R,
       c.H, c.M, pk.packed_src, static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr, nullptr,
-      fill, c.G);
+      pk.kept);
   if (rc != MOE_OK) return rc;
   if (event_between != nullptr &&
       hipEventRecord(static_cast<hipEvent_t>(event_between), st) != hipSuccess)
@@ -889,10 +899,10 @@ int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPackin
   if (scatter_out)
     return launch_bf16_dma<4, 0, 0, false, false, true, true>(
         static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E,
-        R, c.M, c.H, pk.packed_src, nullptr, 0, 0, st, nullptr, nullptr, fill, c.G);
+        R, c.M, c.H, pk.packed_src, nullptr, 0, 0, st, nullptr, nullptr, pk.kept);
   return launch_bf16_dma<4, 0, 0, false, false, true, false>(
       static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(out), c.E, R,
-      c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, fill, c.G);
+      c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, pk.kept);
 }
 
 bool expert_ffn_can_pack(const moe_config& c) {

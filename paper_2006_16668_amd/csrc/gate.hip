@@ -794,6 +794,7 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
         pk.row_base[(size_t)gg * E + e] = run;
         run += fill[(size_t)gg * E + e];
       }
+      pk.kept[e] = run;
     }
   const int s = ch * kChunk + lane;
   const bool valid = s < S;
@@ -873,7 +874,10 @@ __global__ __launch_bounds__(64) void row_maps_from_fill_kernel(
   const int c = (int)(idx % C), g = (int)((idx / C) % G), e = (int)(idx / ((long long)C * G));
   int rb = 0;
   for (int gg = 0; gg < g; ++gg) rb += fill[(size_t)gg * E + e];
-  if (c == 0) pk.row_base[(size_t)g * E + e] = rb;
+  if (c == 0) {
+    pk.row_base[(size_t)g * E + e] = rb;
+    if (g == G - 1) pk.kept[e] = rb + fill[(size_t)g * E + e];
+  }
   if (c < fill[(size_t)g * E + e]) pk.packed_src[(size_t)e * R + rb + c] = (int32_t)idx;
 }
 
@@ -1089,7 +1093,7 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
                      c.C, c.G, nch, hist1, hist2, expert_idx, slot, weight, src_token, c1,
                      mean_gate, aux, static_cast<uint32_t*>(zero_row),
                      zero_row != nullptr ? c.M / 2 : 0, fill,
-                     packing != nullptr ? *packing : RowPacking{nullptr, nullptr});
+                     packing != nullptr ? *packing : RowPacking{nullptr, nullptr, nullptr});
   return check_launch();
 }
 
