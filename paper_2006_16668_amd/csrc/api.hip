@@ -130,9 +130,8 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   // bf16 layers whose shape the persistent GEMM takes skip the dispatched buffer: the first
   // GEMM gathers its rows from x (then the dispatch mark coincides with the gate mark)
   const bool gather = moe::expert_gemm1_can_gather(*cfg);
-  // ... and, in the inference form, multiply only the occupied rows of each expert, packed to
-  // the front of its block (the training form keeps every slot in place for the backward pass)
-  const bool packed = !keep_gates && moe::expert_ffn_can_pack(*cfg);
+  // ... and multiply only the occupied rows of each expert, packed to the front of its block
+  const bool packed = moe::expert_ffn_can_pack(*cfg);
   const moe::RowPacking pk = moe::carve_row_packing(*cfg, base + w.packing);
   if (!mark(0)) return MOE_EHIP;
   rc = moe::launch_gate(*cfg, x, wg, u, expert_idx, slot, weight,
@@ -144,12 +143,13 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
                         packed ? &pk : nullptr, wg_packed, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
-  if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, st);
+  if (!gather) rc = moe::launch_dispatch(*cfg, x, src_token, base + w.buf, nullptr, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
   if (packed) {
     rc = moe::launch_expert_ffn_packed(*cfg, x, pk, base + w.zero_row, wi, wo, base + w.h,
-                                       base + w.out, false, st, events != nullptr ? events[3] : nullptr);
+                                       base + w.out, false, keep_gates ? base + w.signbits : nullptr,
+                                       st, events != nullptr ? events[3] : nullptr);
     if (rc != MOE_OK) return rc;
   } else {
     rc = gather ? moe::launch_expert_gemm1_gather(*cfg, x, src_token, base + w.zero_row, wi,
@@ -310,7 +310,7 @@ int attention_bwd_impl(const moe_config& c, const moe_encoder_dims& d, const voi
   // out = ctx . wo_att
   int rc = moe::launch_dense_wgrad(c, N, A, c.M, ctx, dout, dwo_att, wpart, st);
   if (rc != MOE_OK) return rc;
-  rc = moe::launch_expert_dgrad1(dense_cfg(c, N, A, c.M), dout, wo_att, dctx, st);
+  rc = moe::launch_expert_dgrad1(dense_cfg(c, N, A, c.M), dout, wo_att, dctx, nullptr, st);
   if (rc != MOE_OK) return rc;
   rc = moe::launch_attention_core_bwd(c.act_dtype, qkv, ctx, dctx, lse, dqkv, dvec, d.B, d.L, d.heads,
                                       d.d, st);
@@ -318,7 +318,7 @@ int attention_bwd_impl(const moe_config& c, const moe_encoder_dims& d, const voi
   // qkv = u . wqkv
   rc = moe::launch_dense_wgrad(c, N, c.M, 3 * A, u, dqkv, dwqkv, wpart, st);
   if (rc != MOE_OK) return rc;
-  return moe::launch_expert_dgrad1(dense_cfg(c, N, c.M, 3 * A), dqkv, wqkv, du, st);
+  return moe::launch_expert_dgrad1(dense_cfg(c, N, c.M, 3 * A), dqkv, wqkv, du, nullptr, st);
 }
 
 }  // namespace
@@ -458,7 +458,7 @@ int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token,
   const void* req[] = {x, src_token, buf};
   for (const void* p : req)
     if (p == nullptr || !aligned16(p)) return MOE_EINVAL;
-  return moe::launch_dispatch(*cfg, x, src_token, buf, static_cast<hipStream_t>(stream));
+  return moe::launch_dispatch(*cfg, x, src_token, buf, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int moe_forward_packs_rows(const moe_config* cfg, int* packed) {
@@ -498,7 +498,8 @@ int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, 
     void* zero_row = static_cast<char*>(ws) + maps;
     int r = moe::launch_row_maps_from_fill(*cfg, fill, pk, zero_row, st);
     if (r != MOE_OK) return r;
-    return moe::launch_expert_ffn_packed(*cfg, buf, pk, zero_row, wi, wo, h_ws, out, true, st, nullptr);
+    return moe::launch_expert_ffn_packed(*cfg, buf, pk, zero_row, wi, wo, h_ws, out, true, nullptr, st,
+                                         nullptr);
   }
   const int rc1 = moe::launch_expert_gemm1(*cfg, buf, wi, h_ws, st);
   if (rc1 != MOE_OK) return rc1;
@@ -570,25 +571,31 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
                           reinterpret_cast<moe::bf16_t*>(base + b.wgp),
                           reinterpret_cast<float*>(base + b.dxg),
                           reinterpret_cast<float*>(base + b.dwg_partial)};
+  // the training forward packed the occupied rows of each expert when the shape allows it:
+  // h, out and the row maps in its workspace are in that layout, and so are dout, dh, dbuf, buf
+  const bool packed = moe::expert_ffn_can_pack(*cfg);
+  const moe::RowPacking pk = moe::carve_row_packing(*cfg, const_cast<char*>(fb) + f.packing);
+  const int32_t* kept = packed ? pk.kept : nullptr;
+  const int32_t* rows_src = packed ? pk.packed_src : src_token;
   if (!mark(0)) return MOE_EHIP;
-  rc = moe::launch_combine_bwd(*cfg, dy, fb + f.out, src_token, expert_idx, weight, base + b.dout,
-                               dweight, st);
+  rc = moe::launch_combine_bwd(*cfg, dy, fb + f.out, rows_src, expert_idx, weight, base + b.dout,
+                               dweight, kept, st);
   if (rc != MOE_OK) return rc;
   if (!mark(1)) return MOE_EHIP;
   rc = moe::launch_expert_dgrad2(*cfg, base + b.dout, wo, fb + f.h,
                                  moe::expert_gemm1_can_gather(*cfg) ? fb + f.signbits : nullptr,
-                                 base + b.dh, st);
+                                 base + b.dh, kept, st);
   if (rc != MOE_OK) return rc;
   if (!mark(2)) return MOE_EHIP;
-  rc = moe::launch_expert_wgrad2(*cfg, fb + f.h, base + b.dout, dwo, st);
+  rc = moe::launch_expert_wgrad2(*cfg, fb + f.h, base + b.dout, dwo, kept, st);
   if (rc != MOE_OK) return rc;
   if (!mark(3)) return MOE_EHIP;
-  rc = moe::launch_expert_dgrad1(*cfg, base + b.dh, wi, base + b.dbuf, st);
+  rc = moe::launch_expert_dgrad1(*cfg, base + b.dh, wi, base + b.dbuf, kept, st);
   if (rc != MOE_OK) return rc;
   if (!mark(4)) return MOE_EHIP;
-  rc = moe::launch_dispatch(*cfg, x, src_token, base + b.buf, st);
+  rc = moe::launch_dispatch(*cfg, x, rows_src, base + b.buf, kept, st);
   if (rc != MOE_OK) return rc;
-  rc = moe::launch_expert_wgrad1(*cfg, base + b.buf, base + b.dh, dwi, st);
+  rc = moe::launch_expert_wgrad1(*cfg, base + b.buf, base + b.dh, dwi, kept, st);
   if (rc != MOE_OK) return rc;
   if (!mark(5)) return MOE_EHIP;
   rc = moe::launch_gate_bwd(*cfg, x, wg, reinterpret_cast<const float*>(fb + f.gates), expert_idx,
@@ -596,7 +603,8 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
                             dwg, st);
   if (rc != MOE_OK) return rc;
   if (!mark(6)) return MOE_EHIP;
-  rc = moe::launch_dx(*cfg, wg, base + b.dbuf, expert_idx, slot, gw, dx, st);
+  rc = moe::launch_dx(*cfg, wg, base + b.dbuf, expert_idx, slot, gw, dx,
+                      packed ? pk.row_base : nullptr, st);
   if (rc != MOE_OK) return rc;
   return mark(7) ? MOE_OK : MOE_EHIP;
 }
@@ -841,11 +849,11 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
     const moe_config fc = dense_cfg(*cfg, N, cfg->M, cfg->H);
     rc = moe::launch_dense_wgrad(*cfg, N, cfg->H, cfg->M, f + e.hden, g1, g->w2, wpart, st);
     if (rc != MOE_OK) return rc;
-    rc = moe::launch_expert_dgrad2(fc, g1, w->w2, f + e.hden, nullptr, base + bw.dhden, st);
+    rc = moe::launch_expert_dgrad2(fc, g1, w->w2, f + e.hden, nullptr, base + bw.dhden, nullptr, st);
     if (rc != MOE_OK) return rc;
     rc = moe::launch_dense_wgrad(*cfg, N, cfg->M, cfg->H, f + e.n[1], base + bw.dhden, g->w1, wpart, st);
     if (rc != MOE_OK) return rc;
-    rc = moe::launch_expert_dgrad1(fc, base + bw.dhden, w->w1, dn, st);
+    rc = moe::launch_expert_dgrad1(fc, base + bw.dhden, w->w1, dn, nullptr, st);
     if (rc != MOE_OK) return rc;
   }
   rc = moe::launch_layer_norm_bwd(dt, f + e.a, dn, w->ln_gamma[1], g1, g0, partial, g->ln_gamma[1],

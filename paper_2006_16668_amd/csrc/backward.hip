@@ -29,20 +29,29 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(
     const uint4* __restrict__ dy, const uint4* __restrict__ out,
     const int32_t* __restrict__ src_token, const int32_t* __restrict__ expert_idx,
     const float* __restrict__ weight, uint4* __restrict__ dout, float* __restrict__ dweight,
-    int S, int G, int C, int vec_per_row, long long rows) {
+    int S, int G, int C, int vec_per_row, long long rows, const int32_t* __restrict__ kept) {
   const long long r = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (r >= rows) return;
   const int lane = threadIdx.x & 63;
   const int g = (int)((r / C) % G);
   const int e = (int)(r / ((long long)G * C));
-  const int t = src_token[r];
+  // kept != NULL: packed rows.  src_token then holds the token row g*S + s of packed row p of
+  // expert e for p < kept[e]; the rows up to the end of the last occupied 256-row tile become
+  // zero rows (they enter the weight gradients' sums), later rows are nobody's business.
+  int t = src_token[r];
+  if (kept != nullptr) {
+    const long long p = r - (long long)e * G * C;
+    const int ke = kept[e];
+    if (p >= ((ke + 255) & ~255)) return;
+    if (p >= ke) t = -1;
+  }
   uint4* dst = dout + r * vec_per_row;
   if (t < 0) {
     const uint4 zero = {0u, 0u, 0u, 0u};
     for (int v = lane; v < vec_per_row; v += 64) dst[v] = zero;
     return;
   }
-  const long long n = (long long)g * S + t;
+  const long long n = kept != nullptr ? (long long)t : (long long)g * S + t;
   const int k = expert_idx[2 * n] == e ? 0 : 1;        // the two experts of a token differ
   const float w = weight[2 * n + k];
   const uint4* dyr = dy + n * vec_per_row;
@@ -121,14 +130,25 @@ __global__ __launch_bounds__(256) void wg_pack_bwd_kernel(
 __global__ __launch_bounds__(256) void dx_rows_kernel(
     const float4* __restrict__ dxg, const uint4* __restrict__ dbuf,
     const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ slot,
-    uint4* __restrict__ dx, int S, int G, int C, int vec_per_row, long long tokens) {
+    uint4* __restrict__ dx, int S, int G, int C, int E, int vec_per_row, long long tokens,
+    const int32_t* __restrict__ row_base) {
   const long long n = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (n >= tokens) return;
   const int lane = threadIdx.x & 63;
   const int g = (int)(n / S);
   const int s0 = slot[2 * n], s1 = slot[2 * n + 1];
-  const uint4* r0 = s0 >= 0 ? dbuf + (((long long)expert_idx[2 * n] * G + g) * C + s0) * vec_per_row : nullptr;
-  const uint4* r1 = s1 >= 0 ? dbuf + (((long long)expert_idx[2 * n + 1] * G + g) * C + s1) * vec_per_row : nullptr;
+  // row of a kept choice: (e G + g) C + slot, or e G C + row_base[g,e] + slot when packed
+  const uint4 *r0 = nullptr, *r1 = nullptr;
+  if (s0 >= 0) {
+    const long long e = expert_idx[2 * n];
+    r0 = dbuf + (row_base != nullptr ? e * G * C + row_base[(long long)g * E + e] + s0
+                                     : (e * G + g) * C + s0) * vec_per_row;
+  }
+  if (s1 >= 0) {
+    const long long e = expert_idx[2 * n + 1];
+    r1 = dbuf + (row_base != nullptr ? e * G * C + row_base[(long long)g * E + e] + s1
+                                     : (e * G + g) * C + s1) * vec_per_row;
+  }
   for (int v = lane; v < vec_per_row; v += 64) {
     const float4 a = dxg[(n * vec_per_row + v) * 2], b = dxg[(n * vec_per_row + v) * 2 + 1];
     float acc[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -217,7 +237,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void dx_kernel(
     const float* __restrict__ dz, const float* __restrict__ wg, const T* __restrict__ dbuf,
     const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ slot,
-    T* __restrict__ dx, int S, int G, int C, int M, int E, long long tokens) {
+    T* __restrict__ dx, int S, int G, int C, int M, int E, long long tokens,
+    const int32_t* __restrict__ row_base) {
   __shared__ float zs[16][65];
   __shared__ float ws[16][65];
   const long long n0 = (long long)blockIdx.x * 64;
@@ -256,7 +277,9 @@ __global__ __launch_bounds__(256) void dx_kernel(
     for (int k = 0; k < 2; ++k) {
       const int c = slot[2 * n + k];
       if (c < 0) continue;
-      const T* row = dbuf + (((size_t)expert_idx[2 * n + k] * G + g) * C + c) * M;
+      const size_t e = (size_t)expert_idx[2 * n + k];
+      const T* row = dbuf + (row_base != nullptr ? e * G * C + row_base[(size_t)g * E + e] + c
+                                                 : (e * G + g) * C + c) * M;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int m = m0 + 4 * tm + j;
@@ -361,7 +384,7 @@ int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a
 
 int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
                        const int32_t* src_token, const int32_t* expert_idx, const float* weight,
-                       void* dout, float* dweight, hipStream_t st) {
+                       void* dout, float* dweight, const int32_t* kept, hipStream_t st) {
   const int elt = c.act_dtype == MOE_F32 ? 4 : 2;
   const int vec_per_row = c.M * elt / 16;
   const long long rows = (long long)c.E * c.G * c.C;
@@ -370,12 +393,12 @@ int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
     hipLaunchKernelGGL(combine_bwd_kernel<float>, dim3(grid), dim3(256), 0, st,
                        static_cast<const uint4*>(dy), static_cast<const uint4*>(out), src_token,
                        expert_idx, weight, static_cast<uint4*>(dout), dweight, c.S, c.G, c.C,
-                       vec_per_row, rows);
+                       vec_per_row, rows, kept);
   else
     hipLaunchKernelGGL(combine_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st,
                        static_cast<const uint4*>(dy), static_cast<const uint4*>(out), src_token,
                        expert_idx, weight, static_cast<uint4*>(dout), dweight, c.S, c.G, c.C,
-                       vec_per_row, rows);
+                       vec_per_row, rows, kept);
   return check_launch();
 }
 
@@ -446,7 +469,8 @@ int launch_gate_bwd(const moe_config& c, const void* x, const float* wg, const f
 }
 
 int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int32_t* expert_idx,
-              const int32_t* slot, const GateBwdWs& w, void* dx, hipStream_t st) {
+              const int32_t* slot, const GateBwdWs& w, void* dx, const int32_t* row_base,
+              hipStream_t st) {
   const GateBwdPlan p = gate_bwd_plan(c);
   const long long tokens = (long long)c.G * c.S;
   if (p.mfma) {
@@ -461,7 +485,8 @@ int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int3
     const unsigned grid = (unsigned)((tokens + kRowsPerBlock - 1) / kRowsPerBlock);
     hipLaunchKernelGGL(dx_rows_kernel, dim3(grid), dim3(256), 0, st,
                        reinterpret_cast<const float4*>(w.dxg), static_cast<const uint4*>(dbuf),
-                       expert_idx, slot, static_cast<uint4*>(dx), c.S, c.G, c.C, c.M / 8, tokens);
+                       expert_idx, slot, static_cast<uint4*>(dx), c.S, c.G, c.C, c.E, c.M / 8, tokens,
+                       row_base);
     return check_launch();
   }
   const dim3 grid((unsigned)((tokens + 63) / 64), (unsigned)((c.M + 63) / 64));
@@ -469,11 +494,11 @@ int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int3
   if (c.act_dtype == MOE_F32)
     hipLaunchKernelGGL(dx_kernel<float>, grid, dim3(256), 0, st, w.dz, wg,
                        static_cast<const float*>(dbuf), expert_idx, slot, static_cast<float*>(dx),
-                       c.S, c.G, c.C, c.M, c.E, tokens);
+                       c.S, c.G, c.C, c.M, c.E, tokens, row_base);
   else
     hipLaunchKernelGGL(dx_kernel<bf16_t>, grid, dim3(256), 0, st, w.dz, wg,
                        static_cast<const bf16_t*>(dbuf), expert_idx, slot,
-                       static_cast<bf16_t*>(dx), c.S, c.G, c.C, c.M, c.E, tokens);
+                       static_cast<bf16_t*>(dx), c.S, c.G, c.C, c.M, c.E, tokens, row_base);
   return check_launch();
 }
 

@@ -132,8 +132,9 @@ int launch_gate_pack(const moe_config& c, const float* wg, void* packed, hipStre
 int launch_row_maps_from_fill(const moe_config& c, const int32_t* fill, const RowPacking& pk,
                               void* zero_row, hipStream_t st);
 size_t gate_workspace_bytes(const moe_config& c);
+// kept: NULL, or the packed layout's row counts (src_token is then its packed_src)
 int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token, void* buf,
-                    hipStream_t st);
+                    const int32_t* kept, hipStream_t st);
 // row_base: NULL (out is [E,G,C,M]) or the [G,E] offsets of the packed row layout
 int launch_combine(const moe_config& c, const void* out, const int32_t* expert_idx,
                    const int32_t* slot, const float* weight, const int32_t* row_base, void* y,
@@ -155,7 +156,8 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 bool expert_ffn_can_pack(const moe_config& c);
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
                              const void* zero_row, const void* wi, const void* wo, void* h,
-                             void* out, bool scatter_out, hipStream_t st, void* event_between);
+                             void* out, bool scatter_out, void* signbits, hipStream_t st,
+                             void* event_between);
 inline size_t expert_signbits_bytes(const moe_config& c) {
   return (size_t)c.E * c.G * c.C * c.H / 8;
 }
@@ -163,7 +165,7 @@ inline size_t expert_signbits_bytes(const moe_config& c) {
 // backward pass (backward.hip); epi of the strided GEMM: 0 none, 1 relu, 2 zero where mask <= 0
 int launch_combine_bwd(const moe_config& c, const void* dy, const void* out,
                        const int32_t* src_token, const int32_t* expert_idx, const float* weight,
-                       void* dout, float* dweight, hipStream_t st);
+                       void* dout, float* dweight, const int32_t* kept, hipStream_t st);
 // Gate gradients: on bf16 layers whose token count and M are multiples of 256 the two
 // projections (dwg = x^T dz, dz . wg^T) run on the matrix cores; otherwise fp32 FMA kernels.
 struct GateBwdPlan {
@@ -185,7 +187,8 @@ int launch_gate_bwd(const moe_config& c, const void* x, const float* wg, const f
                     const int32_t* c1, const float* daux, const GateBwdWs& w, float* dwg,
                     hipStream_t st);
 int launch_dx(const moe_config& c, const float* wg, const void* dbuf, const int32_t* expert_idx,
-              const int32_t* slot, const GateBwdWs& w, void* dx, hipStream_t st);
+              const int32_t* slot, const GateBwdWs& w, void* dx, const int32_t* row_base,
+              hipStream_t st);
 int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a_e, long long a_r,
                         long long a_k, const void* B, long long b_e, long long b_k, long long b_n,
                         void* Cout, const void* mask, int R, int N, int K, hipStream_t st);
@@ -195,14 +198,16 @@ int launch_gemm_strided(const moe_config& c, int epi, const void* A, long long a
 //   wgrad2: dwo  = h^T . dout                        [rows,H]^T x [rows,M] -> [H,M]
 //   dgrad1: dbuf = dh . wi^T                         [rows,H] x [M,H]^T -> [rows,M]
 //   wgrad1: dwi  = buf^T . dh                        [rows,M]^T x [rows,H] -> [M,H]
+// kept: NULL, or the row counts of the packed layout (then rows are packed rows: the data
+// gradients walk the occupied row tiles only and the weight gradients sum over them only)
 int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
-                         const void* signbits, void* dh, hipStream_t st);
+                         const void* signbits, void* dh, const int32_t* kept, hipStream_t st);
 int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
-                         hipStream_t st);
+                         const int32_t* kept, hipStream_t st);
 int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,
-                         hipStream_t st);
+                         const int32_t* kept, hipStream_t st);
 int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
-                         hipStream_t st);
+                         const int32_t* kept, hipStream_t st);
 
 // batched bf16 MFMA GEMM with an fp32 result (expert_gemm.hip): transposed_a ? C = A^T.B with
 // A [batch,K,R], B [batch,K,N] : C = A.B^T with A [batch,R,K], B [batch,N,K]; C [batch,R,N]

@@ -15,15 +15,23 @@ constexpr int kRowsPerBlock = 4;  // one wavefront per row
 // rows are M*sizeof(T) bytes, a multiple of 16
 __global__ __launch_bounds__(256) void dispatch_kernel(
     const uint4* __restrict__ x, const int32_t* __restrict__ src_token, uint4* __restrict__ buf,
-    int S, int G, int C, int vec_per_row, long long rows) {
+    int S, int G, int C, int vec_per_row, long long rows, const int32_t* __restrict__ kept) {
   const long long r = (long long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (r >= rows) return;
   const int lane = threadIdx.x & 63;
   const int g = (int)((r / C) % G);
-  const int t = src_token[r];
+  // kept != NULL: packed rows (src_token holds token rows g*S + s for the first kept[e] rows of
+  // expert e; zero rows up to the end of the last occupied 256-row tile, nothing beyond)
+  int t = src_token[r];
+  if (kept != nullptr) {
+    const long long e = r / ((long long)G * C), p = r - e * G * C;
+    const int ke = kept[e];
+    if (p >= ((ke + 255) & ~255)) return;
+    if (p >= ke) t = -1;
+  }
   uint4* dst = buf + r * vec_per_row;
   if (t >= 0) {
-    const uint4* src = x + ((long long)g * S + t) * vec_per_row;
+    const uint4* src = x + (kept != nullptr ? (long long)t : (long long)g * S + t) * vec_per_row;
     for (int v = lane; v < vec_per_row; v += 64) dst[v] = src[v];
   } else {
     const uint4 zero = {0u, 0u, 0u, 0u};
@@ -83,13 +91,13 @@ __global__ __launch_bounds__(256) void combine_kernel(
 }  // namespace
 
 int launch_dispatch(const moe_config& c, const void* x, const int32_t* src_token, void* buf,
-                    hipStream_t st) {
+                    const int32_t* kept, hipStream_t st) {
   const int elt = c.act_dtype == MOE_F32 ? 4 : 2;
   const int vec_per_row = c.M * elt / 16;
   const long long rows = (long long)c.E * c.G * c.C;
   const unsigned grid = (unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock);
   hipLaunchKernelGGL(dispatch_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint4*>(x),
-                     src_token, static_cast<uint4*>(buf), c.S, c.G, c.C, vec_per_row, rows);
+                     src_token, static_cast<uint4*>(buf), c.S, c.G, c.C, vec_per_row, rows, kept);
   return check_launch();
 }
 

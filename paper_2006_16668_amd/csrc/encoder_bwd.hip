@@ -305,7 +305,7 @@ int launch_dense_wgrad(const moe_config& c, long long rows, int in, int out, con
   if (sp <= 1 || partial == nullptr) {
     moe_config g = c;
     g.E = 1; g.G = 1; g.C = (int)rows; g.M = in; g.H = out;
-    return launch_expert_wgrad1(g, X, dY, dW, st);
+    return launch_expert_wgrad1(g, X, dY, dW, nullptr, st);
   }
   const int rc = launch_gemm_bf16_f32out(true, X, dY, partial, sp, in, out, (int)(rows / sp), st);
   if (rc != MOE_OK) return rc;

@@ -885,13 +885,20 @@ int launch_expert_gemm1_gather(const moe_config& c, const void* x, const int32_t
 // the absolute rows pk.packed_src names.
 int launch_expert_ffn_packed(const moe_config& c, const void* a, const RowPacking& pk,
                              const void* zero_row, const void* wi, const void* wo, void* h,
-                             void* out, bool scatter_out, hipStream_t st, void* event_between) {
+                             void* out, bool scatter_out, void* signbits, hipStream_t st,
+                             void* event_between) {
   if (!expert_ffn_can_pack(c)) return MOE_EUNSUPPORTED;
   const int R = c.G * c.C;
-  int rc = launch_bf16_dma<4, 1, 2, false, false, true>(
-      static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(h), c.E, R,
-      c.H, c.M, pk.packed_src, static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr, nullptr,
-      pk.kept);
+  int rc = signbits != nullptr
+               ? launch_bf16_dma<4, 4, 2, false, false, true>(
+                     static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi),
+                     static_cast<bf16_t*>(h), c.E, R, c.H, c.M, pk.packed_src,
+                     static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr,
+                     static_cast<unsigned char*>(signbits), pk.kept)
+               : launch_bf16_dma<4, 1, 2, false, false, true>(
+                     static_cast<const bf16_t*>(a), static_cast<const bf16_t*>(wi),
+                     static_cast<bf16_t*>(h), c.E, R, c.H, c.M, pk.packed_src,
+                     static_cast<const bf16_t*>(zero_row), c.S, c.C, st, nullptr, nullptr, pk.kept);
   if (rc != MOE_OK) return rc;
   if (event_between != nullptr &&
       hipEventRecord(static_cast<hipEvent_t>(event_between), st) != hipSuccess)
@@ -924,8 +931,15 @@ int launch_expert_gemm2(const moe_config& c, const void* h, const void* wo, void
 
 // ---- backward pass: A K-contiguous x B K-contiguous (dgrad), A and B row(k)-major (wgrad) ----
 int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, const void* h,
-                         const void* signbits, void* dh, hipStream_t st) {
+                         const void* signbits, void* dh, const int32_t* kept, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (kept != nullptr) {
+    if (signbits == nullptr || !expert_ffn_can_pack(c)) return MOE_EINVAL;
+    return launch_bf16_dma<4, 5, 0, false, true, true>(
+        static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
+        c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, nullptr,
+        const_cast<unsigned char*>(static_cast<const unsigned char*>(signbits)), kept);
+  }
   // the forward pass recorded the sign bits exactly when its first GEMM gathered (K >= 128)
   if (signbits != nullptr && expert_gemm1_can_gather(c))
     return launch_bf16_dma<4, 5, 0, false, true>(
@@ -941,8 +955,14 @@ int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, 
 }
 
 int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, void* dwo,
-                         hipStream_t st) {
+                         const int32_t* kept, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (kept != nullptr) {
+    if (!expert_ffn_can_pack(c)) return MOE_EINVAL;
+    return launch_bf16_dma<4, 0, 0, true, false, false, false, true>(
+        static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dwo),
+        c.E, c.H, c.M, (int)R, nullptr, nullptr, 0, 0, st, nullptr, nullptr, kept);
+  }
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.H, c.M, (int)R))
     return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dwo),
@@ -952,8 +972,14 @@ int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, v
 }
 
 int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, void* dbuf,
-                         hipStream_t st) {
+                         const int32_t* kept, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (kept != nullptr) {
+    if (!expert_ffn_can_pack(c)) return MOE_EINVAL;
+    return launch_bf16_dma<4, 0, 0, false, true, true>(
+        static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(dbuf),
+        c.E, (int)R, c.M, c.H, nullptr, nullptr, 0, 0, st, nullptr, nullptr, kept);
+  }
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok((int)R, c.M, c.H))
     return launch_bf16_dma<4, 0, 0, false, true>(
         static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(dbuf),
@@ -963,8 +989,14 @@ int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, vo
 }
 
 int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, void* dwi,
-                         hipStream_t st) {
+                         const int32_t* kept, hipStream_t st) {
   const long long R = (long long)c.G * c.C;
+  if (kept != nullptr) {
+    if (!expert_ffn_can_pack(c)) return MOE_EINVAL;
+    return launch_bf16_dma<4, 0, 0, true, false, false, false, true>(
+        static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dwi),
+        c.E, c.M, c.H, (int)R, nullptr, nullptr, 0, 0, st, nullptr, nullptr, kept);
+  }
   if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL && dma_shape_ok(c.M, c.H, (int)R))
     return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dwi),
