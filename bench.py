@@ -294,7 +294,7 @@ def time_f32_layer(moe, cfg, K, W):
     sh = moe.MoEShape(c32.G, c32.S, c32.M, c32.H, c32.E, c32.C, "f32")
     y = torch.empty_like(inp.x)
     aux = torch.empty(c32.G, dtype=torch.float32, device=dev)
-    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    ws = torch.empty(moe.moe_train_workspace_bytes(sh), dtype=torch.uint8, device=dev)
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(moe.binding.FORWARD_EVENTS)]
     for e in evs:
         e.record()
@@ -356,7 +356,8 @@ def measure_forward(moe, cfg, inp, K, W, power=False):
     sh = moe.MoEShape(cfg.G, cfg.S, cfg.M, cfg.H, cfg.E, cfg.C, cfg.act_dtype)
     y = torch.empty_like(inp.x)
     aux = torch.empty(cfg.G, dtype=torch.float32, device=dev)
-    ws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    # (sized for the training forward, which the backward measurement runs in the same buffer)
+    ws = torch.empty(moe.moe_train_workspace_bytes(sh), dtype=torch.uint8, device=dev)
     # occupied expert rows (algorithmic work of the GEMMs counts kept rows only)
     i32 = dict(dtype=torch.int32, device=dev)
     f32 = dict(dtype=torch.float32, device=dev)
@@ -383,12 +384,21 @@ def measure_forward(moe, cfg, inp, K, W, power=False):
     for _ in range(W):
         moe.moe_forward_prepacked(sh, inp.x, inp.wg, wgp, inp.u, inp.wi, inp.wo, y, aux, ws)
     torch.cuda.synchronize()
+    # the timed region: K calls of the layer with the six stage marks recorded between the
+    # kernels, on the kernels' stream
     t0 = time.perf_counter()
     for k in range(K):
         moe.moe_forward_prepacked(sh, inp.x, inp.wg, wgp, inp.u, inp.wi, inp.wo, y, aux, ws, events[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    # the same with wg packed inside every call (moe_forward)
+    # the same K calls without the marks (an event record leaves a gap of about a microsecond
+    # between two kernels)
+    v0 = time.perf_counter()
+    for k in range(K):
+        moe.moe_forward_prepacked(sh, inp.x, inp.wg, wgp, inp.u, inp.wi, inp.wo, y, aux, ws)
+    torch.cuda.synchronize()
+    plain_ms = (time.perf_counter() - v0) * 1e3 / K
+    # and with wg packed inside every call (moe_forward)
     u0 = time.perf_counter()
     for k in range(K):
         moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, ws)
@@ -405,7 +415,7 @@ def measure_forward(moe, cfg, inp, K, W, power=False):
     per_call = {n: sorted(events[k][i].elapsed_time(events[k][i + 1]) for k in range(K))
                 for i, n in enumerate(STAGES)}
     return {"sh": sh, "ws": ws, "y": y, "aux": aux, "wall_s": t1 - t0, "power": pw,
-            "ms_per_step_packing_wg_in_call": repack_ms,
+            "ms_per_step_packing_wg_in_call": repack_ms, "ms_per_step_without_stage_events": plain_ms,
             "kept_rows": kept_rows, "padded_rows": padded_rows, "multiplied_rows": multiplied_rows,
             "stage_ms": {n: sum(v) / K for n, v in per_call.items()},
             "stage_median": {n: v[K // 2] for n, v in per_call.items()},
@@ -482,6 +492,7 @@ def other_config(moe, name, K, W):
     out = {"workload": workload_name(cfg), "tokens": cfg.N, "steps": K, "warmup": W,
            "tokens_per_s": cfg.N * K / m["wall_s"], "ms_per_step": m["wall_s"] * 1e3 / K,
            "ms_per_step_packing_wg_in_call": m["ms_per_step_packing_wg_in_call"],
+           "ms_per_step_without_stage_events": m["ms_per_step_without_stage_events"],
            "kept_rows": m["kept_rows"], "padded_rows": m["padded_rows"],
            "multiplied_rows": m["multiplied_rows"],
            "stages_ms": m["stage_ms"], "stages_ms_min": m["stage_min"],
@@ -564,6 +575,7 @@ def main():
                    "entry_point": "moe_forward_prepacked (gate weights in MFMA operand form, packed once "
                                   "by moe_gate_pack outside the timed region)"},
         "ms_per_step_packing_wg_in_call": m["ms_per_step_packing_wg_in_call"],
+        "ms_per_step_without_stage_events": m["ms_per_step_without_stage_events"],
         "roofline": headline_roofline(moe, cfg, m, roofs),
         "power_state": m["power"],
         "stages_ms": stage_ms, "stages_ms_median": m["stage_median"], "stages_ms_min": m["stage_min"],

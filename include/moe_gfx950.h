@@ -10,13 +10,26 @@
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major,
  *     contiguous, 16-byte aligned.  The config struct is a HOST pointer.
- *   - The library allocates nothing, frees nothing, never synchronises the
- *     device and keeps no state between calls.  Scratch memory comes from the
- *     caller's workspace (size: moe_workspace_bytes / moe_gate_workspace_bytes).
+ *   - The library allocates nothing, frees nothing and never synchronises the
+ *     device.  Scratch memory comes from the caller's workspace (size:
+ *     moe_workspace_bytes / moe_gate_workspace_bytes); nothing a call computes
+ *     survives it outside the caller's buffers.  The only state the library
+ *     keeps is per-device set-up that does not depend on any argument: kernels
+ *     that use more than 64 KB of LDS have that limit raised by a host-side
+ *     attribute call before their first launch on a device, the number of compute
+ *     units is read once, and moe_gate_noalloc looks up the address of its array.
+ *     moe_prepare() does all of it for the current device; otherwise the first
+ *     call that launches such a kernel does it (thread-safe, idempotent).  A
+ *     caller that records a HIP graph calls moe_prepare() (or the entry point
+ *     itself once) before starting the capture.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and the call returns immediately.
  *   - Return value: MOE_OK or a negative moe_status.  Nothing is enqueued when
  *     an argument check fails.  No exception or abort crosses the boundary.
+ *     MOE_EHIP reports what hipPeekAtLastError() says after a launch, so an error
+ *     that earlier work of the caller left pending on the host thread is
+ *     reported by the next launch here as well; the error itself stays in place
+ *     for the caller's own hipGetLastError().
  *   - Activations / expert weights / buffers have the element type
  *     cfg->act_dtype (fp32 or bf16).  The gate path (wg, u, gates, weights,
  *     auxiliary loss) is always fp32.  bf16 expert GEMMs accumulate in fp32; the
@@ -42,7 +55,8 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 typedef enum {
   MOE_OK = 0,
   MOE_EINVAL = -1,       /* null / misaligned pointer, non-positive dimension, E < 2, C < 1 */
-  MOE_EUNSUPPORTED = -2, /* a shape the kernels do not tile (see moe_expert_ffn) */
+  MOE_EUNSUPPORTED = -2, /* a shape the kernels do not take: M or H not a multiple of 16 bytes
+                            (8 bf16 / 4 fp32 elements), more than 2^30 tokens or 2^31 slots */
   MOE_EWORKSPACE = -3,   /* workspace too small */
   MOE_EHIP = -4          /* a kernel launch failed; hipGetLastError() is left for the caller */
 } moe_status;
@@ -58,12 +72,21 @@ typedef struct {
 /* Human-readable name of a status code (static string, never NULL). */
 const char* moe_status_string(int status);
 
+/* One-time set-up of the current device (see the conventions above): LDS limits of the
+ * kernels, compute-unit count, address of moe_gate_noalloc's array.  Host-side queries and
+ * attribute calls only: no allocation, no launch, no synchronisation.  Optional. */
+int moe_prepare(void);
+
 /* Bytes of workspace moe_gate needs for this config.  Pure host function. */
 int moe_gate_workspace_bytes(const moe_config* cfg, size_t* bytes);
 
 /* Bytes of workspace moe_forward needs (routing tensors, expert buffers and the
  * gate scratch).  Pure host function. */
 int moe_workspace_bytes(const moe_config* cfg, size_t* bytes);
+
+/* Bytes of workspace moe_forward_train needs: moe_workspace_bytes plus what only the backward
+ * pass reads (the softmax gates [G,S,E] fp32 and one bit per element of h).  Pure host function. */
+int moe_train_workspace_bytes(const moe_config* cfg, size_t* bytes);
 
 /*
  * Top2Gating: Algorithm 1 of the paper for G independent groups (Section 2.2,
@@ -162,7 +185,6 @@ int moe_dispatch(const moe_config* cfg, const void* x, const int32_t* src_token,
  * in ws), multiply whole 256-row tiles of them and store each result row at its slot of out;
  * the slots c >= fill[g,e] of out are then NOT written (combine never reads them).  Occupied
  * rows get bit-identical results either way.
- * bf16 requires M % 8 == 0 and H % 8 == 0 (16-byte rows), else MOE_EUNSUPPORTED.
  */
 int moe_expert_ffn_workspace_bytes(const moe_config* cfg, size_t* bytes);
 int moe_expert_ffn(const moe_config* cfg, const void* buf, const int32_t* fill, const void* wi,
@@ -245,8 +267,8 @@ int moe_forward_prepacked(const moe_config* cfg, const void* x, const float* wg,
 
 /*
  * moe_forward that also keeps the softmax gates g[G,S,E] (fp32) in the workspace, which
- * the backward pass reads together with the routing tensors, h and out.  Same arguments,
- * results and workspace size as moe_forward.
+ * the backward pass reads together with the routing tensors, h and out.  Same arguments
+ * and results as moe_forward; ws: at least moe_train_workspace_bytes(cfg).
  */
 int moe_forward_train(const moe_config* cfg, const void* x, const float* wg, const float* u,
                       const void* wi, const void* wo, void* y, float* aux,
@@ -267,7 +289,7 @@ int moe_backward_workspace_bytes(const moe_config* cfg, size_t* bytes);
  * in : x, wg, wi, wo as given to the forward call;  dy [G,S,M] act_dtype;
  *      daux [G] fp32 (gradient of the loss with respect to each group's l_aux);
  *      fwd_ws: the workspace that a moe_forward_train call with the same cfg, x, wg, u,
- *      wi, wo has filled (read only here; fwd_ws_bytes >= moe_workspace_bytes)
+ *      wi, wo has filled (read only here; fwd_ws_bytes >= moe_train_workspace_bytes)
  * out: dx [G,S,M] act_dtype;  dwg [M,E] fp32;  dwi [E,M,H], dwo [E,H,M] act_dtype.
  *      Every output element is written (no accumulation into previous contents).
  * ws : at least moe_backward_workspace_bytes(cfg), 256-byte aligned, overwritten.

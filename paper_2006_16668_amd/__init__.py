@@ -13,7 +13,7 @@ from .binding import (EncoderDims, moe_add_layer_norm, moe_attention_workspace_b
                       moe_forward_train, MoEError, MoEShape, library_path, load_library, moe_combine, moe_dispatch,
                       moe_expert_ffn, moe_expert_ffn_workspace_bytes, moe_forward_packs_rows, moe_forward, moe_forward_events, moe_forward_fuses_dispatch,
                       moe_gate, moe_gate_pack, moe_gate_pack_bytes, moe_gate_prepacked, moe_forward_prepacked, moe_gate_noalloc, moe_gate_noalloc_max_bytes, moe_gate_workspace_bytes,
-                      moe_status_string, moe_workspace_bytes)
+                      moe_prepare, moe_status_string, moe_train_workspace_bytes, moe_workspace_bytes)
 
 __all__ = ["EncoderDims", "moe_add_layer_norm", "moe_attention_workspace_bytes", "moe_dense_ffn",
            "moe_encoder_pair_forward", "moe_encoder_workspace_bytes", "moe_self_attention",
@@ -23,4 +23,4 @@ __all__ = ["EncoderDims", "moe_add_layer_norm", "moe_attention_workspace_bytes",
            "moe_forward_train", "MoEError", "MoEShape", "library_path", "load_library", "moe_combine", "moe_dispatch",
            "moe_expert_ffn", "moe_expert_ffn_workspace_bytes", "moe_forward_packs_rows", "moe_forward", "moe_forward_events", "moe_forward_fuses_dispatch",
            "moe_gate", "moe_gate_pack", "moe_gate_pack_bytes", "moe_gate_prepacked", "moe_forward_prepacked", "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_gate_workspace_bytes",
-           "moe_status_string", "moe_workspace_bytes"]
+           "moe_prepare", "moe_status_string", "moe_train_workspace_bytes", "moe_workspace_bytes"]

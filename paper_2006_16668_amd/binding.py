@@ -20,7 +20,7 @@ _lib = None
 MOE_F32, MOE_BF16 = 0, 1
 SLOT_OVERFLOW, SLOT_NOT_SAMPLED = -1, -2
 
-EXPORTS = ("moe_status_string", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_gate",
+EXPORTS = ("moe_status_string", "moe_prepare", "moe_gate_workspace_bytes", "moe_workspace_bytes", "moe_train_workspace_bytes", "moe_gate",
            "moe_gate_noalloc", "moe_gate_noalloc_max_bytes", "moe_dispatch",
            "moe_gate_pack_bytes", "moe_gate_pack", "moe_gate_prepacked", "moe_forward_prepacked",
            "moe_expert_ffn_workspace_bytes", "moe_forward_packs_rows", "moe_expert_ffn", "moe_combine", "moe_forward", "moe_forward_events",
@@ -108,6 +108,7 @@ def load_library() -> ctypes.CDLL:
     for name, args in {
         "moe_gate_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
+        "moe_train_workspace_bytes": [cfgp, ctypes.POINTER(sz)],
         "moe_forward_fuses_dispatch": [cfgp, ctypes.POINTER(i32)],
         "moe_gate": [cfgp] + [vp] * 13 + [sz, vp],
         "moe_gate_noalloc": [cfgp] + [vp] * 13,
@@ -149,6 +150,14 @@ def load_library() -> ctypes.CDLL:
         fn.argtypes = args
     _lib = lib
     return lib
+
+
+def moe_prepare():
+    """One-time set-up of the current device (kernel attributes); optional."""
+    lib = load_library()
+    lib.moe_prepare.restype = ctypes.c_int
+    lib.moe_prepare.argtypes = []
+    _check(lib.moe_prepare(), "moe_prepare")
 
 
 def moe_status_string(status: int) -> str:
@@ -206,6 +215,14 @@ def moe_workspace_bytes(shape: MoEShape) -> int:
     c = shape._c()
     _check(load_library().moe_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
            "moe_workspace_bytes")
+    return n.value
+
+
+def moe_train_workspace_bytes(shape: MoEShape) -> int:
+    n = ctypes.c_size_t(0)
+    c = shape._c()
+    _check(load_library().moe_train_workspace_bytes(ctypes.byref(c), ctypes.byref(n)),
+           "moe_train_workspace_bytes")
     return n.value
 
 

@@ -38,8 +38,9 @@ int check_config(const moe_config* c) {
   if (c == nullptr) return MOE_EINVAL;
   if (c->G < 1 || c->S < 1 || c->M < 1 || c->H < 1 || c->E < 2 || c->C < 1) return MOE_EINVAL;
   if (c->act_dtype != MOE_F32 && c->act_dtype != MOE_BF16) return MOE_EINVAL;
-  // rows are moved and multiplied in 16-byte pieces
-  if (c->M % 8 != 0 || c->H % 8 != 0) return MOE_EUNSUPPORTED;
+  // rows are moved and multiplied in 16-byte pieces: 8 bf16 or 4 fp32 elements
+  const int piece = c->act_dtype == MOE_F32 ? 4 : 8;
+  if (c->M % piece != 0 || c->H % piece != 0) return MOE_EUNSUPPORTED;
   if ((long long)c->G * c->S > 0x3fffffffLL) return MOE_EUNSUPPORTED;
   if ((long long)c->E * c->G * c->C > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   return MOE_OK;
@@ -51,7 +52,8 @@ struct ForwardWs {
       signbits, buf, h, out, gate_ws, total;
 };
 
-ForwardWs carve(const moe_config& c) {
+// train: also the regions only the backward pass reads (softmax gates, relu sign bits)
+ForwardWs carve(const moe_config& c, bool train) {
   const size_t N = (size_t)c.G * c.S, GE = (size_t)c.G * c.E, rows = (size_t)c.E * c.G * c.C;
   const size_t elt = c.act_dtype == MOE_F32 ? 4 : 2;
   ForwardWs w{};
@@ -66,9 +68,9 @@ ForwardWs carve(const moe_config& c) {
   w.mean_gate = take(GE * 4);
   w.zero_row = take((size_t)c.M * elt);
   w.packing = take(moe::expert_ffn_can_pack(c) ? moe::row_packing_bytes(c) : 0);
-  w.gates = take(N * c.E * 4);
-  w.signbits = take(moe::expert_gemm1_can_gather(c) ? moe::expert_signbits_bytes(c) : 0);
-  w.buf = take(rows * c.M * elt);
+  w.gates = take(train ? N * c.E * 4 : 0);
+  w.signbits = take(train && moe::expert_gemm1_can_gather(c) ? moe::expert_signbits_bytes(c) : 0);
+  w.buf = take(moe::expert_gemm1_can_gather(c) ? 0 : rows * c.M * elt);   // gathered from x instead
   w.h = take(rows * c.H * elt);
   w.out = take(rows * c.M * elt);
   w.gate_ws = take(moe::gate_workspace_bytes(c));
@@ -115,7 +117,7 @@ int forward_impl(const moe_config* cfg, const void* x, const float* wg, const fl
   if (events != nullptr)
     for (int i = 0; i < MOE_FORWARD_EVENTS; ++i)
       if (events[i] == nullptr) return MOE_EINVAL;
-  const ForwardWs w = carve(*cfg);
+  const ForwardWs w = carve(*cfg, keep_gates);
   if (ws_bytes < w.total) return MOE_EWORKSPACE;
   char* base = static_cast<char*>(ws);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -220,7 +222,7 @@ EncoderWs carve_enc(const moe_config& c, const moe_encoder_dims& d) {
   w.c = take(N * c.M * elt);
   w.hden = take(N * c.H * elt);
   w.att = take(carve_att(c, d).total);
-  w.moe = take(carve(c).total);
+  w.moe = take(carve(c, false).total);
   w.total = off;
   return w;
 }
@@ -255,7 +257,7 @@ EncoderTrainWs carve_enc_train(const moe_config& c, const moe_encoder_dims& d) {
     w.ctx[i] = take(N * A * elt);
     w.lse[i] = take((size_t)d.B * d.heads * d.L * sizeof(float));
   }
-  w.moe = take(carve(c).total);
+  w.moe = take(carve(c, true).total);
   w.total = off;
   return w;
 }
@@ -336,6 +338,15 @@ const char* moe_status_string(int status) {
   }
 }
 
+int moe_prepare(void) {
+  int rc = moe::prepare_expert_gemm();
+  if (rc == MOE_OK) rc = moe::prepare_gate();
+  if (rc == MOE_OK) rc = moe::prepare_attention_bwd();
+  void* p = nullptr;
+  if (rc == MOE_OK) rc = gate_scratch_ptr(&p);
+  return rc;
+}
+
 int moe_gate_workspace_bytes(const moe_config* cfg, size_t* bytes) {
   const int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
@@ -348,7 +359,15 @@ int moe_workspace_bytes(const moe_config* cfg, size_t* bytes) {
   const int rc = check_config(cfg);
   if (rc != MOE_OK) return rc;
   if (bytes == nullptr) return MOE_EINVAL;
-  *bytes = carve(*cfg).total;
+  *bytes = carve(*cfg, false).total;
+  return MOE_OK;
+}
+
+int moe_train_workspace_bytes(const moe_config* cfg, size_t* bytes) {
+  const int rc = check_config(cfg);
+  if (rc != MOE_OK) return rc;
+  if (bytes == nullptr) return MOE_EINVAL;
+  *bytes = carve(*cfg, true).total;
   return MOE_OK;
 }
 
@@ -551,7 +570,7 @@ int moe_backward_events(const moe_config* cfg, const void* x, const float* wg, c
   if (events != nullptr)
     for (int i = 0; i < MOE_BACKWARD_EVENTS; ++i)
       if (events[i] == nullptr) return MOE_EINVAL;
-  const ForwardWs f = carve(*cfg);
+  const ForwardWs f = carve(*cfg, true);
   const BackwardWs b = carve_bwd(*cfg);
   if (fwd_ws_bytes < f.total || ws_bytes < b.total) return MOE_EWORKSPACE;
   const char* fb = static_cast<const char*>(fwd_ws);
@@ -726,7 +745,7 @@ int moe_encoder_pair_forward(const moe_config* cfg, const moe_encoder_dims* dims
   if (rc != MOE_OK) return rc;
   rc = moe::launch_add_layer_norm(dt, b, sub, w->ln_gamma[3], w->ln_beta[3], c, norm, N, cfg->M, st);
   if (rc != MOE_OK) return rc;
-  rc = forward_impl(cfg, norm, w->wg, u, w->wi, w->wo, sub, aux, base + e.moe, carve(*cfg).total,
+  rc = forward_impl(cfg, norm, w->wg, u, w->wi, w->wo, sub, aux, base + e.moe, carve(*cfg, false).total,
                     stream, nullptr, false);
   if (rc != MOE_OK) return rc;
   return moe::launch_add_rows(dt, c, sub, y, N * cfg->M, st);
@@ -791,7 +810,7 @@ int moe_encoder_pair_forward_train(const moe_config* cfg, const moe_encoder_dims
   rc = moe::launch_add_layer_norm(dt, b, sub, w->ln_gamma[3], w->ln_beta[3], c, base + e.n[3], N, cfg->M, st);
   if (rc != MOE_OK) return rc;
   rc = forward_impl(cfg, base + e.n[3], w->wg, u, w->wi, w->wo, sub, aux, base + e.moe,
-                    carve(*cfg).total, stream, nullptr, true);
+                    carve(*cfg, true).total, stream, nullptr, true);
   if (rc != MOE_OK) return rc;
   return moe::launch_add_rows(dt, c, sub, y, N * cfg->M, st);
 }
@@ -829,7 +848,7 @@ int moe_encoder_pair_backward(const moe_config* cfg, const moe_encoder_dims* dim
   auto lse = [&](int i) { return reinterpret_cast<const float*>(f + e.lse[i]); };
 
   // y = c + MoE(n4): the MoE layer's gradients; dn = d L / d n4
-  rc = moe_backward(cfg, f + e.n[3], w->wg, w->wi, w->wo, dy, daux, f + e.moe, carve(*cfg).total, dn,
+  rc = moe_backward(cfg, f + e.n[3], w->wg, w->wi, w->wo, dy, daux, f + e.moe, carve(*cfg, true).total, dn,
                     g->wg, g->wi, g->wo, base + bw.moe, carve_bwd(*cfg).total, stream);
   if (rc != MOE_OK) return rc;
   // g0 = d L / d c = dy + LN4'(dn)

@@ -31,7 +31,6 @@
 namespace moe {
 namespace {
 
-constexpr int kMaxDevices = 64;   // devices one process can address (per-device launch caches)
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
@@ -345,25 +344,26 @@ __global__ __launch_bounds__(256, 1) void attention_bwd_dkv_mfma_kernel(
 }
 
 template <int D>
+int prepare_bwd() {
+  using GM = AttBwdGeom<D>;
+  constexpr int kLdsQ = 2 * GM::kRowBlock + GM::kTrBlock;      // one stage
+  constexpr int kLdsKV = 2 * (2 * GM::kRowBlock + 2 * GM::kTrBlock + 512);
+  static_assert(kLdsKV <= 160 * 1024, "two stages must fit the 160 KB of LDS");
+  static LdsLimitOnce once_q, once_kv;
+  const int rc = ensure_lds_limit(once_q, reinterpret_cast<const void*>(attention_bwd_dq_mfma_kernel<D>), kLdsQ);
+  if (rc != MOE_OK) return rc;
+  return ensure_lds_limit(once_kv, reinterpret_cast<const void*>(attention_bwd_dkv_mfma_kernel<D>), kLdsKV);
+}
+
+template <int D>
 int launch_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse,
                bf16_t* dqkv, float* dvec, long long B, int L, int heads, hipStream_t st) {
   using GM = AttBwdGeom<D>;
   constexpr int kLdsQ = 2 * GM::kRowBlock + GM::kTrBlock;      // one stage
   constexpr int kLdsKV = 2 * (2 * GM::kRowBlock + 2 * GM::kTrBlock + 512);
-  static_assert(kLdsKV <= 160 * 1024, "two stages must fit the 160 KB of LDS");
   auto kq = attention_bwd_dq_mfma_kernel<D>;
   auto kkv = attention_bwd_dkv_mfma_kernel<D>;
-  static bool attr_set[kMaxDevices] = {};      // per device; setting it twice is harmless
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kq),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsQ) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(kkv),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsKV) != hipSuccess)
-      return MOE_EHIP;
-    attr_set[dev] = true;
-  }
+  if (prepare_bwd<D>() != MOE_OK) return MOE_EHIP;
   const long long blocks = B * heads * (L / 128);
   if (blocks > 0x7fffffffLL) return MOE_EUNSUPPORTED;
   hipLaunchKernelGGL(kq, dim3((unsigned)blocks), dim3(256), kLdsQ, st, qkv, ctx, dctx, lse, dqkv, dvec,
@@ -377,6 +377,11 @@ int launch_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const f
 
 bool attention_bwd_mfma_ok(int act_dtype, int L, int d) {
   return act_dtype == MOE_BF16 && (d == 64 || d == 128) && L % 128 == 0;
+}
+
+int prepare_attention_bwd() {
+  const int rc = prepare_bwd<64>();
+  return rc != MOE_OK ? rc : prepare_bwd<128>();
 }
 
 int launch_attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse,

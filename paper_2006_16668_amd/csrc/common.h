@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "../../include/moe_gfx950.h"
 
 namespace moe {
@@ -257,5 +258,26 @@ int launch_attention_core_bwd(int act_dtype, const void* qkv, const void* ctx, c
                               int heads, int d, hipStream_t st);
 
 inline int check_launch() { return hipPeekAtLastError() == hipSuccess ? MOE_OK : MOE_EHIP; }
+
+// A kernel that uses more than 64 KB of dynamic LDS needs its limit raised once per device
+// before its first launch.  Every launcher of such a kernel calls ensure_lds_limit (cheap after
+// the first time, safe from several host threads: the flag is atomic and setting the attribute
+// twice is harmless); the prepare_* functions do the same for every such kernel of a source
+// file up front, so that the first real call has nothing left to set up.
+constexpr int kMaxDevices = 64;   // devices one process can address
+struct LdsLimitOnce { std::atomic<int> done[kMaxDevices]; };
+inline int ensure_lds_limit(LdsLimitOnce& once, const void* kernel, int bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
+  if (once.done[dev].load(std::memory_order_acquire) != 0) return MOE_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return MOE_EHIP;
+  once.done[dev].store(1, std::memory_order_release);
+  return MOE_OK;
+}
+int compute_units(int* cus);      // of the current device (cached per device)
+int prepare_expert_gemm();        // expert_gemm.hip
+int prepare_gate();               // gate.hip
+int prepare_attention_bwd();      // attention_bwd_mfma.hip
 
 }  // namespace moe

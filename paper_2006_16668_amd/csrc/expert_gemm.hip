@@ -1,19 +1,28 @@
 // Expert networks (Eq. 2 of the paper; Algorithm 2: EGCM,EMH->EGCH, relu,
-// EGCH,EHM->EGCM) as two grouped GEMMs over the experts:
+// EGCH,EHM->EGCM) as two grouped GEMMs over the experts, and the four GEMMs of
+// their backward pass:
 //
 //   h[e]   = relu(buf[e] . wi[e])     [R, M] x [M, H],  R = G*C rows per expert
 //   out[e] = h[e] . wo[e]             [R, H] x [H, M]
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  A tiles (row-major,
-// K contiguous) sit in LDS as [m][k] and are read with 16-byte loads; the weight
-// tiles are [k][n] in memory (N contiguous), stay that way in LDS and are read
-// with ds_read_b64_tr_b16, which hands every lane the 4 consecutive k of its
-// column that the MFMA B operand wants.  Global -> register -> LDS double
-// buffering, one barrier per K step.  Blocks are renumbered so that each XCD
-// (own L2) walks a contiguous range of tiles with the row tile varying fastest:
-// neighbours share one weight panel.
+// bf16, v_mfma_f32_32x32x16_bf16 with fp32 accumulation, in two kernels:
 //
-// fp32 path: plain LDS-tiled FMA kernel (small reference-precision configs).
+//   expert_gemm_bf16_dma_kernel   shapes made of whole 256x256 tiles with K % 32 == 0
+//     (every benchmarked layer): persistent, one block per CU walks its share of the
+//     tiles as one stream of K steps; operands travel global -> LDS without passing
+//     the registers; either operand in either layout; gathered rows, packed rows,
+//     scattered result rows and a per-expert k range as template options.
+//   expert_gemm_bf16_kernel       every other shape: one block per tile, operands
+//     staged global -> registers -> LDS (double buffered, one barrier per K step),
+//     clamped addresses and select masks at the ragged edges.
+//
+// In both, activation tiles (K contiguous) sit in LDS as [m][k] and are read with
+// 16-byte loads; weight tiles are [k][n] in memory (N contiguous), stay that way in
+// LDS and are read with ds_read_b64_tr_b16, which hands every lane the 4 consecutive
+// k of its column that the MFMA operand wants.  Blocks of one XCD (own L2) take
+// neighbouring tiles so that they share operand panels.
+//
+// fp32 layers run the fp32 MFMA kernel of gemm_f32.hip.
 #include "common.h"
 
 namespace moe {
@@ -25,7 +34,6 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // native 16-byte vector
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kMaxDevices = 64;   // devices one process can address (per-device launch caches)
 constexpr int kXcds = 8;
 
 __device__ __forceinline__ int xcd_remap(int bid, int nblk) {
@@ -714,6 +722,19 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
 #undef MOE_DMA_MFMA_ROW
 }
 
+// LDS limit of one instantiation of the persistent kernel on the current device (all of the
+// 160 KB when the size depends on the number of experts)
+template <int ST, int EPI, int GATHER, bool A_MNC = false, bool B_KC = false, bool PACKED = false,
+          bool SCATTER = false, bool DYNK = false>
+int prepare_dma() {
+  static LdsLimitOnce once;
+  constexpr int kFixed = (int)DmaSmem<ST>::kBytes + (GATHER ? 1024 : 0) + (EPI == 5 ? 8192 : 0);
+  return ensure_lds_limit(
+      once, reinterpret_cast<const void*>(
+                expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER, DYNK>),
+      PACKED || DYNK ? 160 * 1024 : kFixed);
+}
+
 template <int ST, int EPI, int GATHER, bool A_MNC = false, bool B_KC = false, bool PACKED = false,
           bool SCATTER = false, bool DYNK = false>
 int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
@@ -738,21 +759,10 @@ int launch_bf16_dma(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R
   }
   if ((PACKED || DYNK) && kept == nullptr) return MOE_EINVAL;
   auto kern = expert_gemm_bf16_dma_kernel<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER, DYNK>;
-  // per device, once: the kernel's LDS limit and the number of compute units.  The cached
-  // values are constants of the device, so a race between two first calls is harmless.
-  static int cus_of[kMaxDevices] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
-  if (cus_of[dev] == 0) {
-    int n = 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            PACKED || DYNK ? 160 * 1024 : (int)kLds) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-      return MOE_EHIP;
-    cus_of[dev] = n;
-  }
-  const int cus = cus_of[dev];
+  int cus = 0;
+  if (prepare_dma<ST, EPI, GATHER, A_MNC, B_KC, PACKED, SCATTER, DYNK>() != MOE_OK ||
+      compute_units(&cus) != MOE_OK)
+    return MOE_EHIP;
   const int tiles_m = R / 256, tiles_n = N / 256;
   const long long ntiles = (long long)E * tiles_m * tiles_n;
   if (ntiles > 0x7fffffffLL) return MOE_EUNSUPPORTED;
@@ -770,19 +780,19 @@ inline bool dma_shape_ok(int R, int N, int K) {
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
+int prepare_tiled() {
+  static LdsLimitOnce once;
+  return ensure_lds_limit(
+      once, reinterpret_cast<const void*>(expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>),
+      (int)GemmSmem<BM, BN, BK>::kBytes);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
 int launch_bf16_kernel(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
                        hipStream_t st) {
   using SM = GemmSmem<BM, BN, BK>;
   auto kern = expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>;
-  static bool attr_set[kMaxDevices] = {};   // per device; setting it twice is harmless
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytes) != hipSuccess)
-      return MOE_EHIP;
-    attr_set[dev] = true;
-  }
+  if (prepare_tiled<BM, BN, BK, WM, WN, RELU, EXACT>() != MOE_OK) return MOE_EHIP;
   const int tiles_m = (R + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long nblk = (long long)E * tiles_m * tiles_n;
   if (nblk > 0x7fffffffLL) return MOE_EUNSUPPORTED;
@@ -822,6 +832,47 @@ int gemm_f32(const float* A, const float* B, float* Cout, int E, int R, int N, i
 }
 
 }  // namespace
+
+int compute_units(int* cus) {
+  static std::atomic<int> cus_of[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_EHIP;
+  int n = cus_of[dev].load(std::memory_order_acquire);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      return MOE_EHIP;
+    cus_of[dev].store(n, std::memory_order_release);
+  }
+  *cus = n;
+  return MOE_OK;
+}
+
+// Every instantiation the launchers of this file use (a kernel missing from this list is
+// still set up by its launcher's first call).
+int prepare_expert_gemm() {
+  const int rcs[] = {
+      // forward
+      prepare_dma<4, 1, 0>(), prepare_dma<4, 0, 0>(), prepare_dma<4, 1, 1>(), prepare_dma<4, 4, 1>(),
+      prepare_dma<4, 1, 2, false, false, true>(), prepare_dma<4, 4, 2, false, false, true>(),
+      prepare_dma<4, 0, 0, false, false, true, false>(), prepare_dma<4, 0, 0, false, false, true, true>(),
+      // fp32 results (gate logits and gate gradients)
+      prepare_dma<4, 3, 0, true, false>(), prepare_dma<4, 3, 0, false, true>(),
+      // backward
+      prepare_dma<4, 5, 0, false, true>(), prepare_dma<4, 2, 0, false, true>(),
+      prepare_dma<4, 0, 0, true, false>(), prepare_dma<4, 0, 0, false, true>(),
+      prepare_dma<4, 5, 0, false, true, true>(), prepare_dma<4, 0, 0, false, true, true>(),
+      prepare_dma<4, 0, 0, true, false, false, false, true>(),
+      // ragged shapes
+      prepare_tiled<256, 256, 64, 2, 2, true, true>(), prepare_tiled<256, 256, 64, 2, 2, true, false>(),
+      prepare_tiled<256, 256, 64, 2, 2, false, true>(), prepare_tiled<256, 256, 64, 2, 2, false, false>(),
+      prepare_tiled<128, 128, 64, 2, 2, true, true>(), prepare_tiled<128, 128, 64, 2, 2, true, false>(),
+      prepare_tiled<128, 128, 64, 2, 2, false, true>(), prepare_tiled<128, 128, 64, 2, 2, false, false>()};
+  int cus = 0;
+  if (compute_units(&cus) != MOE_OK) return MOE_EHIP;
+  for (int rc : rcs)
+    if (rc != MOE_OK) return rc;
+  return MOE_OK;
+}
 
 static int rows_per_expert(const moe_config& c, int* R) {
   const long long rows = (long long)c.G * c.C;

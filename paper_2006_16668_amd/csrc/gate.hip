@@ -1013,6 +1013,17 @@ int launch_gate_pack(const moe_config& c, const float* wg, void* packed, hipStre
   return check_launch();
 }
 
+constexpr size_t kGateRowsLds1 = (4 * 128 * 33 + 2 * 32) * 4, kGateRowsLds2 = (4 * 128 * 65 + 2 * 64) * 4;
+
+int prepare_gate() {
+  static LdsLimitOnce once1, once2;
+  const int rc = ensure_lds_limit(once1, reinterpret_cast<const void*>(gate_mfma_rows_kernel<1>),
+                                  (int)kGateRowsLds1);
+  if (rc != MOE_OK) return rc;
+  return ensure_lds_limit(once2, reinterpret_cast<const void*>(gate_mfma_rows_kernel<2>),
+                          (int)kGateRowsLds2);
+}
+
 int launch_gate(const moe_config& c, const void* x, const float* wg, const float* u,
                 int32_t* expert_idx, int32_t* slot, float* weight, int32_t* fill,
                 int32_t* src_token, int32_t* c1, float* mean_gate, float* aux,
@@ -1064,18 +1075,8 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
     const bf16_t* xb = static_cast<const bf16_t*>(x);
 #define MOE_GATE_ARGS xb, wgP, u, c.S, c.M, c.E, nch, expert_idx, slot, weight, gates_opt, hist1, hist2, msum
     if (c.E <= 64) {
-      const size_t lds1 = (4 * 128 * 33 + 2 * 32) * 4, lds2 = (4 * 128 * 65 + 2 * 64) * 4;
-      static bool lds_set[64] = {};                   // per device; setting it twice is harmless
-      int dev = 0;
-      if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_EHIP;
-      if (!lds_set[dev]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gate_mfma_rows_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(gate_mfma_rows_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2) != hipSuccess)
-          return MOE_EHIP;
-        lds_set[dev] = true;
-      }
+      const size_t lds1 = kGateRowsLds1, lds2 = kGateRowsLds2;
+      if (prepare_gate() != MOE_OK) return MOE_EHIP;
       if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, lds1, st, MOE_GATE_ARGS);
       else hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, lds2, st, MOE_GATE_ARGS);
     }

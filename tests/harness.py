@@ -64,7 +64,7 @@ def gpu_forward_backward(cfg: MoEConfig, inp, dy, daux):
     nan = float("nan")
     y = torch.full((cfg.G, cfg.S, cfg.M), nan, dtype=dt, device=dev)
     aux = torch.full((cfg.G,), nan, dtype=torch.float32, device=dev)
-    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=dev)
+    fws = torch.empty(moe.moe_train_workspace_bytes(sh), dtype=torch.uint8, device=dev)
     moe.moe_forward_train(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, fws)
     dx = torch.full((cfg.G, cfg.S, cfg.M), nan, dtype=dt, device=dev)
     dwg = torch.full((cfg.M, cfg.E), nan, dtype=torch.float32, device=dev)

@@ -29,10 +29,12 @@ def test_host_only_entry_points():
     assert "unknown" in moe.moe_status_string(-99)
     sh = moe.MoEShape(8, 4096, 1024, 8192, 32, 256, "bf16")
     rows = sh.E * sh.G * sh.C
-    need = rows * (2 * sh.M + sh.H) * 2           # buf + out + h
-    need += rows * sh.H // 8                      # one bit per element of h, kept for the backward pass
+    need = rows * (sh.M + sh.H) * 2               # out + h (the rows of buf are gathered from x)
     got = moe.moe_workspace_bytes(sh)
     assert need < got < need + (16 << 20)
+    # training keeps the softmax gates and one bit per element of h for the backward pass
+    extra = sh.G * sh.S * sh.E * 4 + rows * sh.H // 8
+    assert got + extra <= moe.moe_train_workspace_bytes(sh) < got + extra + (1 << 20)
     assert 0 < moe.moe_gate_workspace_bytes(sh) < got
     # the paper-size bf16 layer gathers inside the first GEMM; fp32 and short rows do not
     assert moe.moe_forward_fuses_dispatch(sh) is True

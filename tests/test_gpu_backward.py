@@ -93,7 +93,7 @@ def test_backward_argument_errors():
     inp = make_inputs(cfg, device=DEV)
     dy, daux = make_upstream(cfg, device=DEV)
     f32 = dict(dtype=torch.float32, device=DEV)
-    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    fws = torch.empty(moe.moe_train_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
     bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
     dx, dwg = torch.empty((1, 64, 32), **f32), torch.empty((32, 4), **f32)
     dwi, dwo = torch.empty((4, 32, 64), **f32), torch.empty((4, 64, 32), **f32)

@@ -61,6 +61,8 @@ SMALL_CASES = [
     # fp32 expert GEMMs on the matrix cores: several 128 x 128 tiles with ragged tails in rows,
     # columns and K (rows per expert = 303, no multiple of 4 either)
     MoEConfig("f32_tiles", G=3, S=200, M=136, H=264, E=3, C=101, act_dtype="f32", seed=37),
+    # fp32 rows need 16 bytes = 4 elements only
+    MoEConfig("f32_quads", G=3, S=90, M=36, H=44, E=5, C=21, act_dtype="f32", seed=48),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
     # the layer call packs the occupied rows of an expert to the front of its block and multiplies
     # only the 256-row tiles that hold them: skewed routing (full and nearly empty experts), far
@@ -218,8 +220,12 @@ def test_argument_errors_enqueue_nothing():
         moe.moe_forward(sh, inp.x, inp.wg, inp.u, inp.wi, inp.wo, y, aux, small_ws)
     assert ei.value.status == -3
     with pytest.raises(moe.MoEError) as ei:
-        moe.moe_workspace_bytes(moe.MoEShape(1, 64, 30, 64, 4, 32, "f32"))   # M % 8 != 0
+        moe.moe_workspace_bytes(moe.MoEShape(1, 64, 30, 64, 4, 32, "f32"))   # fp32: M % 4 != 0
     assert ei.value.status == -2
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_workspace_bytes(moe.MoEShape(1, 64, 36, 64, 4, 32, "bf16"))  # bf16: M % 8 != 0
+    assert ei.value.status == -2
+    assert moe.moe_workspace_bytes(moe.MoEShape(1, 64, 36, 64, 4, 32, "f32")) > 0
     with pytest.raises(moe.MoEError) as ei:
         moe.moe_workspace_bytes(moe.MoEShape(1, 64, 32, 64, 1, 32, "f32"))   # E < 2
     assert ei.value.status == -1
@@ -293,18 +299,14 @@ def test_forward_and_backward_replay_from_a_hip_graph():
     y = torch.empty_like(x)
     aux = torch.empty(cfg.G, dtype=torch.float32, device=DEV)
     dx, dwg, dwi, dwo = torch.empty_like(x), torch.empty_like(wg), torch.empty_like(wi), torch.empty_like(wo)
-    fws = torch.empty(moe.moe_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
+    fws = torch.empty(moe.moe_train_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
     bws = torch.empty(moe.moe_backward_workspace_bytes(sh), dtype=torch.uint8, device=DEV)
 
     def step():
         moe.moe_forward_train(sh, x, wg, u, wi, wo, y, aux, fws)
         moe.moe_backward(sh, x, wg, wi, wo, dy, daux, fws, dx, dwg, dwi, dwo, bws)
 
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        step()                                        # first call outside capture: one-time kernel attributes
-    torch.cuda.current_stream().wait_stream(side)
+    moe.moe_prepare()                                 # one-time kernel attributes, before the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
