@@ -21,7 +21,8 @@ by eye:
                                    only to cross-check the sequential form
 * ``dense_combine_weights``    -- Section 3.1: the [G,S,E,C] combine_weights tensor
                                    and the binary dispatch_mask
-* ``moe_forward_einsum``       -- Algorithm 2, the einsums as printed (tiny inputs)
+* ``moe_forward_dense``        -- Algorithm 2 / Section 3.1: the layer as sums over the dense
+                                   [G,S,E,C] tensors (tiny inputs)
 * ``expert_hidden``            -- Eq. 2, inner half:  ReLU(wi_e . x)
 * ``expert_ffn``               -- Eq. 2:  FFN_e(x) = wo_e . ReLU(wi_e . x)
 * ``moe_forward``              -- Eq. 1-3:  y_s = sum_e G_{s,e} FFN_e(x_s)
@@ -110,41 +111,45 @@ def top2_gating_group(gates, u, C, literal_pass2=False):
     gates = _f64(gates)
     u = _f64(u)
     S, E = gates.shape
-    c = np.zeros(E, dtype=np.int64)                       # c_E <- 0
-    m = gates.sum(axis=0) / S                             # m_E
+    # every token's two largest gates and their normalised values (the same in both passes: R4)
+    picks = [top_2(gates[s]) for s in range(S)]
+    first = [(e1, g1 / (g1 + g2)) for (g1, e1, g2, e2) in picks]
+    second = [(e2, g2 / (g1 + g2)) for (g1, e1, g2, e2) in picks]
+
+    c = np.zeros(E, dtype=np.int64)                       # running count of tokens sent to each expert
+    m = gates.sum(axis=0) / S                             # mean gate per expert
     combine = np.zeros((S, E))
     expert_idx = np.zeros((S, 2), dtype=np.int64)
     slot = np.full((S, 2), SLOT_OVERFLOW, dtype=np.int64)
     weight = np.zeros((S, 2))
 
-    for s in range(S):                                    # first pass
-        g1, e1, g2, e2 = top_2(gates[s])
-        g1 = g1 / (g1 + g2)
+    # pass 1: first choices in token order; an expert that is full turns the token away but
+    # still counts it
+    for s, (e1, g1n) in enumerate(first):
         pos = c[e1]
         expert_idx[s, 0] = e1
         if pos < C:
-            combine[s, e1] = g1
+            combine[s, e1] = g1n
             slot[s, 0] = pos
-            weight[s, 0] = g1
+            weight[s, 0] = g1n
         c[e1] = pos + 1
 
     c1 = c.copy()
-    aux = float(np.sum((c / S) * m) / E)                  # l_aux, before pass 2
+    aux = float(np.sum((c / S) * m) / E)                  # l_aux from the counts as they stand now (R2)
 
-    for s in range(S):                                    # second pass
-        g1, e1, g2, e2 = top_2(gates[s])
-        g2 = g2 / (g1 + g2)
-        rnd = u[s]
+    # pass 2: second choices queue behind all first choices; a token takes part with
+    # probability proportional to its second gate (2 g2n > uniform)
+    for s, (e2, g2n) in enumerate(second):
         pos = c[e2]
-        sampled = (2.0 * g2 > rnd)
+        sampled = (2.0 * g2n > u[s])
         expert_idx[s, 1] = e2
         if pos < C and sampled:
-            combine[s, e2] = g2
+            combine[s, e2] = g2n
             slot[s, 1] = pos
-            weight[s, 1] = g2
+            weight[s, 1] = g2n
         elif not sampled:
             slot[s, 1] = SLOT_NOT_SAMPLED
-        if sampled or literal_pass2:                      # reading R1
+        if sampled or literal_pass2:                      # R1: a token that is not sampled takes no place
             c[e2] = pos + 1
 
     return dict(combine=combine, expert_idx=expert_idx, slot=slot, weight=weight,
@@ -240,23 +245,31 @@ def dense_combine_weights(routing, E, C):
     return cw, dm
 
 
-def moe_forward_einsum(x, wg, u, wi, wo, C, literal_pass2=False):
-    """Algorithm 2 with its einsums as printed.  O(G S M E C): tiny inputs only.
+def moe_forward_dense(x, wg, u, wi, wo, C, literal_pass2=False):
+    """The layer through the dense tensors of Section 3.1 (Algorithm 2's formulation).
 
-    The expert outputs are kept as EGCM (reading R7), so the last einsum reads
-    GSEC,EGCM->GSM.
+    Instead of following the routing record, every step is a sum over ALL tokens or ALL
+    buffer positions, weighted by dispatch_mask / combine_weights [G,S,E,C]:
+      slot input   buf[e,g,c,:] = sum_s dispatch_mask[g,s,e,c] x[g,s,:]
+      expert       out[e,g,c,:] = FFN_e(buf[e,g,c,:])                        (Eq. 2)
+      token output y[g,s,:]     = sum_{e,c} combine_weights[g,s,e,c] out[e,g,c,:]
+    written as one small matrix product per (group, expert).  O(G S M E C): tiny inputs
+    only.  The expert outputs stay in [E,G,C,M] order (reading R7).
     """
-    x, wg, wi, wo = _f64(x), _f64(wg), _f64(wi), _f64(wo)
+    x, wg = _f64(x), _f64(wg)
+    G, S, M = x.shape
     E = wg.shape[1]
-    gates = softmax_gates(x, wg)
-    routing = top2_gating(gates, u, C, literal_pass2)
-    combine_weights, dispatch_mask = dense_combine_weights(routing, E, C)
-    dispatched = np.einsum("gsec,gsm->egcm", dispatch_mask, x)
-    h = np.einsum("egcm,emh->egch", dispatched, wi)
-    h = np.maximum(h, 0.0)
-    expert_outputs = np.einsum("egch,ehm->egcm", h, wo)
-    outputs = np.einsum("gsec,egcm->gsm", combine_weights, expert_outputs)
-    return outputs, routing, dispatched, expert_outputs
+    routing = top2_gating(softmax_gates(x, wg), u, C, literal_pass2)
+    weights_dense, mask_dense = dense_combine_weights(routing, E, C)
+    buf = np.zeros((E, G, C, M))
+    out = np.zeros((E, G, C, M))
+    y = np.zeros((G, S, M))
+    for g in range(G):
+        for e in range(E):
+            buf[e, g] = mask_dense[g, :, e, :].T @ x[g]                  # [C,S] . [S,M]
+            out[e, g] = expert_ffn(buf[e, g], wi[e], wo[e])
+            y[g] += weights_dense[g, :, e, :] @ out[e, g]                # [S,C] . [C,M]
+    return y, routing, buf, out
 
 
 # --------------------------------------------------------------------------

@@ -62,15 +62,15 @@ def test_identical_experts_make_routing_irrelevant():
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_definition_equals_printed_einsums(seed):
-    """Eq. 1-3 evaluated per expert == Algorithm 2's four einsums on the dense
+def test_definition_equals_dense_formulation(seed):
+    """Eq. 1-3 evaluated per expert == Algorithm 2's sums over the dense
     [G,S,E,C] tensors == a per-token sum over the group combine weights G_{S,E}."""
     rng = np.random.default_rng(20 + seed)
     G, S, M, H, E = int(rng.integers(1, 4)), int(rng.integers(2, 20)), 5, 6, int(rng.integers(2, 6))
     C = int(rng.integers(1, 2 * S // E + 3))
     x, wg, u, wi, wo = _rand_layer(rng, G, S, M, H, E)
     y, r, buf, out = orc.moe_forward(x, wg, u, wi, wo, C)
-    y2, r2, buf2, out2 = orc.moe_forward_einsum(x, wg, u, wi, wo, C)
+    y2, r2, buf2, out2 = orc.moe_forward_dense(x, wg, u, wi, wo, C)
     np.testing.assert_allclose(y, y2, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(buf, buf2, rtol=0, atol=0)
     np.testing.assert_allclose(out, out2, rtol=1e-12, atol=1e-13)
