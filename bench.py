@@ -40,7 +40,7 @@ def measured_traffic(cfg_name):
     if not os.path.exists(path):
         return {}, None
     text = open(path).read()
-    fs = re.search(r"FETCH_SIZE is scaled by ([0-9.]+), WRITE_SIZE by ([0-9.]+)", text)
+    fs = re.search(r"FETCH_SIZE is scaled by ([0-9]+(?:\.[0-9]+)?), WRITE_SIZE by ([0-9]+(?:\.[0-9]+)?)", text)
     date = re.search(r"Measured: (\S+)", text)
     if not fs:
         return {}, None
