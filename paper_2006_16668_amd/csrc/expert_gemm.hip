@@ -42,30 +42,48 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblk) {
   return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
-template <int BM, int BN, int BK>
-struct GemmSmem {
-  static constexpr int kAPitch = BK + 8;    // bf16 elements; 16 B pad: conflict-free b128 reads
-  static constexpr int kBPitch = BN + 16;   // 32 B pad: 4 consecutive k rows hit distinct banks
-  static constexpr int kAElems = BM * kAPitch;
-  static constexpr int kBElems = BK * kBPitch;
-  static constexpr size_t kBytes = (size_t)2 * (kAElems + kBElems) * sizeof(bf16_t);
+// LDS staging of one operand tile of ROWS output rows (or columns) x BK.  "K-contiguous"
+// (KC): the operand is stored [rows][K]; staged as [ROWS][BK + 8] (16 B pad: conflict-free
+// 16-byte reads).  "row-of-k" (MNC): stored [K][rows]; staged as [BK][ROWS + 16] (32 B pad:
+// 4 consecutive k rows hit distinct banks) and read with the transposing LDS load.
+template <int ROWS, int BK, bool MNC>
+struct OperandSmem {
+  static constexpr int kPitch = MNC ? ROWS + 16 : BK + 8;
+  static constexpr int kElems = MNC ? BK * kPitch : ROWS * kPitch;
+  static constexpr int kVecs = ROWS * BK / 8 / 256;             // 16-byte vectors per thread
+  static constexpr int kVecsPerLine = MNC ? ROWS / 8 : BK / 8;  // along the contiguous dimension
+  static constexpr int kLinesPerPass = 256 / kVecsPerLine;
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
+template <int BM, int BN, int BK, bool A_MNC, bool B_KC>
+struct GemmSmem {
+  using SA = OperandSmem<BM, BK, A_MNC>;
+  using SB = OperandSmem<BN, BK, !B_KC>;
+  static constexpr size_t kBytes = (size_t)2 * (SA::kElems + SB::kElems) * sizeof(bf16_t);
+};
+
+// One block per 256x256 or 128x128 tile of C, any shape (clamped addresses and select masks at
+// the ragged edges; EXACT drops them), either operand in either layout (the same three products
+// as the persistent kernel below):
+//   C = A . B      A KC [R,K], B MNC [K,N]      C = A . B^T    A KC, B KC [N,K]
+//   C = A^T . B    A MNC [K,R], B MNC [K,N]
+// EPI: 0 plain, 1 relu, 2 zero every element whose `mask` element (same index as C) is <= 0.
+// Contiguous dimensions are multiples of 8 elements (16-byte loads are whole or masked whole).
+template <int BM, int BN, int BK, int WM, int WN, int EPI, bool A_MNC, bool B_KC, bool EXACT>
 __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, bf16_t* __restrict__ Cout,
-    int R, int N, int K, int tiles_m, int tiles_n, int nblk) {
-  using SM = GemmSmem<BM, BN, BK>;
+    const bf16_t* __restrict__ mask, int R, int N, int K, int tiles_m, int tiles_n, int nblk) {
+  using SM = GemmSmem<BM, BN, BK, A_MNC, B_KC>;
+  using SA = typename SM::SA;
+  using SB = typename SM::SB;
   constexpr int WTM = BM / WM, WTN = BN / WN;      // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wave
-  constexpr int AV = BM * BK / 8 / 256;            // 16-byte vectors per thread
-  constexpr int BV = BK * BN / 8 / 256;
   static_assert(WM * WN == 4, "four wavefronts per block");
-  static_assert(AV >= 1 && BV >= 1, "tile too small for 256 threads");
+  static_assert(SA::kVecs >= 1 && SB::kVecs >= 1, "tile too small for 256 threads");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);            // [2][BM][kAPitch]
-  bf16_t* Bs = As + 2 * SM::kAElems;                           // [2][BK][kBPitch]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);            // two stages
+  bf16_t* Bs = As + 2 * SA::kElems;                            // two stages
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int logical = xcd_remap(blockIdx.x, nblk);
@@ -77,57 +95,44 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
 
   const bf16_t* Ae = A + (size_t)e * R * K;
   const bf16_t* Be = B + (size_t)e * K * N;
-  bf16_t* Ce = Cout + (size_t)e * R * N;
+  const size_t c_e = (size_t)e * R * N;
 
-  u32x4_t areg[1][AV], breg[1][BV];   // staging registers of the tile in flight
-  bf16_t* const as_w = As + (tid / (BK / 8)) * SM::kAPitch + (tid % (BK / 8)) * 8;
-  bf16_t* const bs_w = Bs + (tid / (BN / 8)) * SM::kBPitch + (tid % (BN / 8)) * 8;
-
-  // Loads are branch-free.  EXACT tiles: uniform (scalar) base + one per-lane byte
-  // offset, so the loads of a tile share a single address register.  Ragged tiles:
-  // addresses are clamped into the matrix and lanes that fall outside K or N are
-  // zeroed by a select afterwards.
-  const uint32_t a_lane = (uint32_t)(((tid / (BK / 8)) * K + (tid % (BK / 8)) * 8) * 2);
-  const uint32_t b_lane = (uint32_t)(((tid / (BN / 8)) * N + (tid % (BN / 8)) * 8) * 2);
-  const char* const a_tile = reinterpret_cast<const char*>(Ae + (size_t)m0 * K);
-  const char* const b_tile = reinterpret_cast<const char*>(Be + n0);
-#define MOE_LOAD_TILES(S, k0)                                                                \
-  if (EXACT) {                                                                               \
-    _Pragma("unroll") for (int i = 0; i < AV; ++i)                                           \
-      areg[S][i] = *reinterpret_cast<const u32x4_t*>(                                          \
-          a_tile + ((size_t)(i * (256 / (BK / 8))) * K + (k0)) * 2 + a_lane);                \
-    _Pragma("unroll") for (int i = 0; i < BV; ++i)                                           \
-      breg[S][i] = *reinterpret_cast<const u32x4_t*>(                                          \
-          b_tile + ((size_t)((k0) + i * (256 / (BN / 8))) * N) * 2 + b_lane);                \
-  } else {                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < AV; ++i) {                                         \
-      int gr = m0 + i * (256 / (BK / 8)) + tid / (BK / 8);                                   \
-      int gk = (k0) + (tid % (BK / 8)) * 8;                                                  \
-      gr = gr < R ? gr : R - 1; /* surplus rows are never stored */                          \
-      const bool ok = gk < K;                                                                \
-      gk = ok ? gk : K - 8;                                                                  \
-      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(Ae + (size_t)gr * K + gk);             \
-      areg[S][i] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};                                           \
-    }                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < BV; ++i) {                                         \
-      int gk = (k0) + i * (256 / (BN / 8)) + tid / (BN / 8);                                 \
-      int gn = n0 + (tid % (BN / 8)) * 8;                                                    \
-      const bool ok = gk < K && gn < N;                                                      \
-      gk = gk < K ? gk : K - 1;                                                              \
-      gn = gn < N ? gn : N - 8;                                                              \
-      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(Be + (size_t)gk * N + gn);             \
-      breg[S][i] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};                                           \
+  // One 16-byte vector of an operand tile: `line` counts rows of the operand's memory layout
+  // (output rows / columns for KC, k for MNC), `vec` the position along the contiguous
+  // dimension.  Out-of-range pieces are read from a clamped address and replaced by zeros;
+  // surplus output rows of a KC operand are clamped only (their results are never stored).
+  typedef u32x4_t vec_t;
+#define MOE_LOAD_OPERAND(REGS, SX, MNC, BASE, EXTENT, ORIGIN, k0)                              \
+  _Pragma("unroll") for (int i = 0; i < SX::kVecs; ++i) {                                    \
+    const int line_ = tid / SX::kVecsPerLine + i * SX::kLinesPerPass;                        \
+    const int vec_ = (tid % SX::kVecsPerLine) * 8;                                           \
+    if (MNC) {                                                                               \
+      int gk = (k0) + line_, gx = (ORIGIN) + vec_;                                           \
+      const bool ok = EXACT || (gk < K && gx < (EXTENT));                                    \
+      if (!EXACT) { gk = gk < K ? gk : K - 1; gx = gx < (EXTENT) ? gx : (EXTENT) - 8; }     \
+      const vec_t v = *reinterpret_cast<const vec_t*>((BASE) + (size_t)gk * (EXTENT) + gx);  \
+      REGS[i] = ok ? v : vec_t{0u, 0u, 0u, 0u};                                              \
+    } else {                                                                                 \
+      int gx = (ORIGIN) + line_, gk = (k0) + vec_;                                           \
+      const bool ok = EXACT || gk < K;                                                       \
+      if (!EXACT) { gx = gx < (EXTENT) ? gx : (EXTENT) - 1; gk = gk < K ? gk : K - 8; }     \
+      const vec_t v = *reinterpret_cast<const vec_t*>((BASE) + (size_t)gx * K + gk);         \
+      REGS[i] = ok ? v : vec_t{0u, 0u, 0u, 0u};                                              \
     }                                                                                        \
   }
-#define MOE_STORE_TILES(S, buf)                                                                 \
-  {                                                                                          \
-    _Pragma("unroll") for (int i = 0; i < AV; ++i)                                           \
-      *reinterpret_cast<u32x4_t*>(as_w + (buf) * SM::kAElems +                                 \
-                                i * (256 / (BK / 8)) * SM::kAPitch) = areg[S][i];            \
-    _Pragma("unroll") for (int i = 0; i < BV; ++i)                                           \
-      *reinterpret_cast<u32x4_t*>(bs_w + (buf) * SM::kBElems +                                 \
-                                i * (256 / (BN / 8)) * SM::kBPitch) = breg[S][i];            \
+#define MOE_STORE_OPERAND(REGS, SX, XS, buf)                                                    \
+  _Pragma("unroll") for (int i = 0; i < SX::kVecs; ++i) {                                    \
+    const int line_ = tid / SX::kVecsPerLine + i * SX::kLinesPerPass;                        \
+    const int vec_ = (tid % SX::kVecsPerLine) * 8;                                           \
+    *reinterpret_cast<vec_t*>(XS + (buf) * SX::kElems + line_ * SX::kPitch + vec_) = REGS[i]; \
   }
+  vec_t areg[SA::kVecs], breg[SB::kVecs];          // staging registers of the tile in flight
+#define MOE_LOAD_TILES(k0)                                                                   \
+  MOE_LOAD_OPERAND(areg, SA, A_MNC, Ae, R, m0, k0)                                           \
+  MOE_LOAD_OPERAND(breg, SB, !B_KC, Be, N, n0, k0)
+#define MOE_STORE_TILES(buf)                                                                 \
+  MOE_STORE_OPERAND(areg, SA, As, buf)                                                       \
+  MOE_STORE_OPERAND(breg, SB, Bs, buf)
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -137,30 +142,29 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // per-lane LDS offsets (elements)
-  const int a_off = (wm0 + (lane & 31)) * SM::kAPitch + 8 * (lane >> 5);
-  const int b_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * SM::kBPitch + wn0 +
-                    16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // MFMA operands of one 16-wide k step: each lane gets the 8 consecutive k of one output row
+  // (A) / column (B).  KC: one 16-byte read; MNC: two transposing 8-byte reads.
   typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
-
-  // MFMA operands of one 16-wide k step: A rows of the wave tile, B columns
-  // (each lane: 8 consecutive k of one row / column)
+  const int kc_off_a = (wm0 + (lane & 31)) * SA::kPitch + 8 * (lane >> 5);
+  const int kc_off_b = (wn0 + (lane & 31)) * SB::kPitch + 8 * (lane >> 5);
+  const int mnc_line = 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const int mnc_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   struct Frags { bf16x8_t a[TM]; bf16x8_t b[TN]; };
-#define MOE_READ_FRAGS(F, buf, kk)                                                           \
-  {                                                                                          \
-    const bf16_t* as_ = As + (buf) * SM::kAElems + a_off + (kk) * 16;                        \
-    const bf16_t* bs_ = Bs + (buf) * SM::kBElems + b_off + (kk) * 16 * SM::kBPitch;          \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-      (F).a[i] = *reinterpret_cast<const bf16x8_t*>(as_ + i * 32 * SM::kAPitch);             \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bs_ + j * 32)); \
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(                            \
-          (lds_s16x4_ptr)(bs_ + j * 32 + 4 * SM::kBPitch));                                  \
-      (F).b[j] = __builtin_bit_cast(bf16x8_t,                                                \
-                                    __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
+#define MOE_READ_OPERAND(DST, CNT, SX, MNC, XS, KC_OFF, W0, buf, kk)                           \
+  _Pragma("unroll") for (int i = 0; i < CNT; ++i) {                                          \
+    if (MNC) {                                                                               \
+      const bf16_t* p_ = XS + (buf) * SX::kElems + ((kk) * 16 + mnc_line) * SX::kPitch + (W0) + mnc_col + i * 32; \
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p_);         \
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p_ + 4 * SX::kPitch)); \
+      DST[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7)); \
+    } else {                                                                                 \
+      DST[i] = *reinterpret_cast<const bf16x8_t*>(XS + (buf) * SX::kElems + (KC_OFF) + (kk) * 16 + i * 32 * SX::kPitch); \
     }                                                                                        \
   }
-  // The weight fragment goes in as the first MFMA operand: the 32x32 result is then
+#define MOE_READ_FRAGS(F, buf, kk)                                                           \
+  MOE_READ_OPERAND((F).a, TM, SA, A_MNC, As, kc_off_a, wm0, buf, kk)                         \
+  MOE_READ_OPERAND((F).b, TN, SB, !B_KC, Bs, kc_off_b, wn0, buf, kk)
+  // The B fragment goes in as the first MFMA operand: the 32x32 result is then
   // the transposed tile, i.e. a lane owns 4 consecutive columns of one row of C.
 #define MOE_MFMA_STEP(F)                                                                     \
   _Pragma("unroll") for (int i = 0; i < TM; ++i)                                             \
@@ -173,22 +177,22 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
   // Pipeline: tile kt is consumed from LDS stage kt&1 while tile kt+1 travels
   // through the staging registers (loaded right after the barrier, written to the
   // other LDS stage during the last k step).
-  MOE_LOAD_TILES(0, 0)
-  MOE_STORE_TILES(0, 0)
+  MOE_LOAD_TILES(0)
+  MOE_STORE_TILES(0)
   __syncthreads();
-  if (KT > 1) MOE_LOAD_TILES(0, BK)
+  if (KT > 1) { MOE_LOAD_TILES(BK) }
   MOE_READ_FRAGS(fr[0], 0, 0)
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      if (kk + 1 < KK) MOE_READ_FRAGS(fr[(kk + 1) & 1], cur, kk + 1)
-      if (kk + 1 == KK && kt + 1 < KT) MOE_STORE_TILES(0, cur ^ 1)
+      if (kk + 1 < KK) { MOE_READ_FRAGS(fr[(kk + 1) & 1], cur, kk + 1) }
+      if (kk + 1 == KK && kt + 1 < KT) { MOE_STORE_TILES(cur ^ 1) }
       MOE_MFMA_STEP(fr[kk & 1])
     }
     __syncthreads();
-    if (kt + 2 < KT) MOE_LOAD_TILES(0, (kt + 2) * BK)
-    if (kt + 1 < KT) MOE_READ_FRAGS(fr[0], cur ^ 1, 0)
+    if (kt + 2 < KT) { MOE_LOAD_TILES((kt + 2) * BK) }
+    if (kt + 1 < KT) { MOE_READ_FRAGS(fr[0], cur ^ 1, 0) }
   }
 
   // epilogue: acc[i][j][r] = C[row][col .. col+3 for r%4 = 0..3] with
@@ -201,19 +205,30 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_kernel(
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int col = n0 + wn0 + 32 * j + 8 * q + 4 * (lane >> 5);
+        if (!(EXACT || (row < R && col < N))) continue;   // N % 8 == 0: the 4 columns are in or out together
+        const size_t o = c_e + (size_t)row * N + col;
         float v[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           v[r] = acc[i][j][4 * q + r];
-          if (RELU) v[r] = fmaxf(v[r], 0.f);
+          if (EPI == 1) v[r] = fmaxf(v[r], 0.f);
         }
-        if (EXACT || (row < R && col < N))      // N % 8 == 0: the 4 columns are in or out together
-          *reinterpret_cast<uint2*>(Ce + (size_t)row * N + col) =
-              uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        if (EPI == 2) {
+          const uint2 mk = *reinterpret_cast<const uint2*>(mask + o);
+          // a bf16 is positive iff its bits, read as a 16-bit integer, are positive
+          if ((int16_t)(mk.x & 0xffffu) <= 0) v[0] = 0.f;
+          if ((int16_t)(mk.x >> 16) <= 0) v[1] = 0.f;
+          if ((int16_t)(mk.y & 0xffffu) <= 0) v[2] = 0.f;
+          if ((int16_t)(mk.y >> 16) <= 0) v[3] = 0.f;
+        }
+        *reinterpret_cast<uint2*>(Cout + o) = uint2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
       }
   }
+#undef MOE_READ_OPERAND
 #undef MOE_READ_FRAGS
 #undef MOE_MFMA_STEP
+#undef MOE_LOAD_OPERAND
+#undef MOE_STORE_OPERAND
 #undef MOE_LOAD_TILES
 #undef MOE_STORE_TILES
 }
@@ -779,34 +794,43 @@ inline bool dma_shape_ok(int R, int N, int K) {
   return R % 256 == 0 && N % 256 == 0 && K % 32 == 0 && 256 * big * 2 < (1LL << 31);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
+template <int BM, int BN, int BK, int EPI, bool A_MNC, bool B_KC, bool EXACT>
 int prepare_tiled() {
   static LdsLimitOnce once;
   return ensure_lds_limit(
-      once, reinterpret_cast<const void*>(expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>),
-      (int)GemmSmem<BM, BN, BK>::kBytes);
+      once,
+      reinterpret_cast<const void*>(expert_gemm_bf16_kernel<BM, BN, BK, 2, 2, EPI, A_MNC, B_KC, EXACT>),
+      (int)GemmSmem<BM, BN, BK, A_MNC, B_KC>::kBytes);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU, bool EXACT>
-int launch_bf16_kernel(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
-                       hipStream_t st) {
-  using SM = GemmSmem<BM, BN, BK>;
-  auto kern = expert_gemm_bf16_kernel<BM, BN, BK, WM, WN, RELU, EXACT>;
-  if (prepare_tiled<BM, BN, BK, WM, WN, RELU, EXACT>() != MOE_OK) return MOE_EHIP;
+template <int BM, int BN, int BK, int EPI, bool A_MNC, bool B_KC, bool EXACT>
+int launch_bf16_kernel(const bf16_t* A, const bf16_t* B, bf16_t* Cout, const bf16_t* mask, int E,
+                       int R, int N, int K, hipStream_t st) {
+  using SM = GemmSmem<BM, BN, BK, A_MNC, B_KC>;
+  auto kern = expert_gemm_bf16_kernel<BM, BN, BK, 2, 2, EPI, A_MNC, B_KC, EXACT>;
+  if (prepare_tiled<BM, BN, BK, EPI, A_MNC, B_KC, EXACT>() != MOE_OK) return MOE_EHIP;
   const int tiles_m = (R + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long nblk = (long long)E * tiles_m * tiles_n;
   if (nblk > 0x7fffffffLL) return MOE_EUNSUPPORTED;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), SM::kBytes, st, A, B, Cout, R, N, K,
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), SM::kBytes, st, A, B, Cout, mask, R, N, K,
                      tiles_m, tiles_n, (int)nblk);
   return check_launch();
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool RELU>
-int launch_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int N, int K,
-                hipStream_t st) {
-  if (R % BM == 0 && N % BN == 0 && K % BK == 0)
-    return launch_bf16_kernel<BM, BN, BK, WM, WN, RELU, true>(A, B, Cout, E, R, N, K, st);
-  return launch_bf16_kernel<BM, BN, BK, WM, WN, RELU, false>(A, B, Cout, E, R, N, K, st);
+// C [E,R,N] for any R, N, K with N % 8 == 0 and the operands' contiguous dimensions % 8 == 0
+// (K for a K-contiguous operand, R / N for a row-of-k one): 256x256 tiles when the output is
+// large enough, else 128x128.
+template <int EPI, bool A_MNC, bool B_KC>
+int gemm_bf16_tiled(const bf16_t* A, const bf16_t* B, bf16_t* Cout, const bf16_t* mask, int E, int R,
+                    int N, int K, hipStream_t st) {
+  if (R > 128 && N >= 256) {
+    if (R % 256 == 0 && N % 256 == 0 && K % 64 == 0)
+      return launch_bf16_kernel<256, 256, 64, EPI, A_MNC, B_KC, true>(A, B, Cout, mask, E, R, N, K, st);
+    return launch_bf16_kernel<256, 256, 64, EPI, A_MNC, B_KC, false>(A, B, Cout, mask, E, R, N, K, st);
+  }
+  if (R % 128 == 0 && N % 128 == 0 && K % 64 == 0)
+    return launch_bf16_kernel<128, 128, 64, EPI, A_MNC, B_KC, true>(A, B, Cout, mask, E, R, N, K, st);
+  return launch_bf16_kernel<128, 128, 64, EPI, A_MNC, B_KC, false>(A, B, Cout, mask, E, R, N, K, st);
 }
 
 template <bool RELU>
@@ -815,8 +839,7 @@ int gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* Cout, int E, int R, int 
   if (dma_shape_ok(R, N, K))
     return launch_bf16_dma<4, RELU ? 1 : 0, 0>(A, B, Cout, E, R, N, K, nullptr, nullptr, 0, 0,
                                                    st);
-  if (R > 128 && N >= 256) return launch_bf16<256, 256, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
-  return launch_bf16<128, 128, 64, 2, 2, RELU>(A, B, Cout, E, R, N, K, st);
+  return gemm_bf16_tiled<RELU ? 1 : 0, false, false>(A, B, Cout, nullptr, E, R, N, K, st);
 }
 
 // ---------------------------------------------------------------- fp32 path
@@ -862,11 +885,13 @@ int prepare_expert_gemm() {
       prepare_dma<4, 0, 0, true, false>(), prepare_dma<4, 0, 0, false, true>(),
       prepare_dma<4, 5, 0, false, true, true>(), prepare_dma<4, 0, 0, false, true, true>(),
       prepare_dma<4, 0, 0, true, false, false, false, true>(),
-      // ragged shapes
-      prepare_tiled<256, 256, 64, 2, 2, true, true>(), prepare_tiled<256, 256, 64, 2, 2, true, false>(),
-      prepare_tiled<256, 256, 64, 2, 2, false, true>(), prepare_tiled<256, 256, 64, 2, 2, false, false>(),
-      prepare_tiled<128, 128, 64, 2, 2, true, true>(), prepare_tiled<128, 128, 64, 2, 2, true, false>(),
-      prepare_tiled<128, 128, 64, 2, 2, false, true>(), prepare_tiled<128, 128, 64, 2, 2, false, false>()};
+      // ragged shapes: forward (relu / plain), data gradients (plain / masked), weight gradients
+#define MOE_TILED_BOTH(EPI, AM, BK_)                                                              \
+      prepare_tiled<256, 256, 64, EPI, AM, BK_, true>(), prepare_tiled<256, 256, 64, EPI, AM, BK_, false>(), \
+      prepare_tiled<128, 128, 64, EPI, AM, BK_, true>(), prepare_tiled<128, 128, 64, EPI, AM, BK_, false>()
+      MOE_TILED_BOTH(1, false, false), MOE_TILED_BOTH(0, false, false), MOE_TILED_BOTH(0, false, true),
+      MOE_TILED_BOTH(2, false, true), MOE_TILED_BOTH(0, true, false)};
+#undef MOE_TILED_BOTH
   int cus = 0;
   if (compute_units(&cus) != MOE_OK) return MOE_EHIP;
   for (int rc : rcs)
@@ -1001,6 +1026,11 @@ int launch_expert_dgrad2(const moe_config& c, const void* dout, const void* wo, 
     return launch_bf16_dma<4, 2, 0, false, true>(
         static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo), static_cast<bf16_t*>(dh),
         c.E, (int)R, c.H, c.M, nullptr, nullptr, 0, 0, st, static_cast<const bf16_t*>(h));
+  // other bf16 shapes: the tiled MFMA kernel, A . B^T with the mask epilogue
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL)
+    return gemm_bf16_tiled<2, false, true>(static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(wo),
+                                           static_cast<bf16_t*>(dh), static_cast<const bf16_t*>(h), c.E,
+                                           (int)R, c.H, c.M, st);
   return launch_gemm_strided(c, 2, dout, R * c.M, c.M, 1, wo, (long long)c.H * c.M, 1, c.M, dh, h,
                              (int)R, c.H, c.M, st);
 }
@@ -1018,6 +1048,9 @@ int launch_expert_wgrad2(const moe_config& c, const void* h, const void* dout, v
     return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dwo),
         c.E, c.H, c.M, (int)R, nullptr, nullptr, 0, 0, st);
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL)       // A^T . B on the tiled MFMA kernel
+    return gemm_bf16_tiled<0, true, false>(static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dout),
+                                           static_cast<bf16_t*>(dwo), nullptr, c.E, c.H, c.M, (int)R, st);
   return launch_gemm_strided(c, 0, h, R * c.H, 1, c.H, dout, R * c.M, c.M, 1, dwo, nullptr, c.H,
                              c.M, (int)R, st);
 }
@@ -1035,6 +1068,9 @@ int launch_expert_dgrad1(const moe_config& c, const void* dh, const void* wi, vo
     return launch_bf16_dma<4, 0, 0, false, true>(
         static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi), static_cast<bf16_t*>(dbuf),
         c.E, (int)R, c.M, c.H, nullptr, nullptr, 0, 0, st);
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL)       // A . B^T on the tiled MFMA kernel
+    return gemm_bf16_tiled<0, false, true>(static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(wi),
+                                           static_cast<bf16_t*>(dbuf), nullptr, c.E, (int)R, c.M, c.H, st);
   return launch_gemm_strided(c, 0, dh, R * c.H, c.H, 1, wi, (long long)c.M * c.H, 1, c.H, dbuf,
                              nullptr, (int)R, c.M, c.H, st);
 }
@@ -1052,6 +1088,9 @@ int launch_expert_wgrad1(const moe_config& c, const void* buf, const void* dh, v
     return launch_bf16_dma<4, 0, 0, true, false>(
         static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dwi),
         c.E, c.M, c.H, (int)R, nullptr, nullptr, 0, 0, st);
+  if (c.act_dtype == MOE_BF16 && R <= 0x7fffffffLL)       // A^T . B on the tiled MFMA kernel
+    return gemm_bf16_tiled<0, true, false>(static_cast<const bf16_t*>(buf), static_cast<const bf16_t*>(dh),
+                                           static_cast<bf16_t*>(dwi), nullptr, c.E, c.M, c.H, (int)R, st);
   return launch_gemm_strided(c, 0, buf, R * c.M, 1, c.M, dh, R * c.H, c.H, 1, dwi, nullptr, c.M,
                              c.H, (int)R, st);
 }
