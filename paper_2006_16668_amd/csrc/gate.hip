@@ -314,8 +314,12 @@ __device__ __forceinline__ void gate_chunk_epilogue(
 // dimension and all four 32-token row tiles, so that one fetch of a packed weight fragment
 // (3 KB per MFMA step from L2) feeds 12 MFMAs instead of 3: with one chunk per block the
 // weight fragments cost three times the L2 traffic of x itself.  x goes from global memory
-// straight into the A operand, two 64-feature blocks ahead; the four partial sums meet in LDS
-// and are added in a fixed order.
+// straight into the A operand, two 64-feature blocks ahead, re-requested row tile by row tile
+// as the MFMAs free the registers; the four partial sums meet in LDS.  The epilogue works in
+// registers: two lanes per token read the four partial sums of half a row each (added in a fixed
+// order), so softmax, top-2 and the routing decision need no further pass over LDS; the chunk's
+// gate sums are wavefront butterflies over the 32 tokens of a wavefront, then one addition of
+// the chunk's two wavefronts.
 template <int ET>
 __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
@@ -323,14 +327,26 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int Epad = 32 * ET, pitch = Epad + 1, PD = 2;
+  // pitch = 4 mod 32 floats: the 16-byte reads of 16 lanes (16 token rows, same columns) fall
+  // into 16 different bank groups
+  constexpr int Epad = 32 * ET, pitch = Epad + 4, PD = 2, EPT = Epad / 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char gate_smem[];
   float* part = reinterpret_cast<float*>(gate_smem);            // [4][128 * pitch]
-  int* hh = reinterpret_cast<int*>(part + 4 * 128 * pitch);      // [2 * Epad]
+  float* msw = part + 4 * 128 * pitch;                           // [4 wavefronts][Epad] gate sums
+  int* hh = reinterpret_cast<int*>(msw + 4 * Epad);              // [2 chunks][2][Epad] histograms
   const int npair = (nch + 1) / 2;
   const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
+  // epilogue role: token 32 wave + (lane % 16) + 16 (lane / 32), half (lane / 16) % 2 of its experts;
+  // its random number is requested before everything else
+  const int tk = 32 * wave + (lane & 15) + 16 * (lane >> 5), sub = (lane >> 4) & 1;
+  const int s_ep = pr * 128 + tk;
+  const bool valid = s_ep < S;
+  const size_t n_ep = (size_t)g * S + (valid ? s_ep : 0);
+  const float u_n = u[n_ep];
+  for (int i = threadIdx.x; i < 4 * Epad; i += 256) hh[i] = 0;   // ordered by the barrier after the K loop
+
   const bf16_t* xrow[4];
 #pragma unroll
   for (int rt = 0; rt < 4; ++rt) {
@@ -355,20 +371,22 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
   // zero weights in the packed operand).
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
   u32x4_t a[PD][4][4];
-#define MOE_GATE_LOAD_X2(P, KBI)                                                      \
+#define MOE_GATE_LOAD_XROW(P, KBI, rt)                                                \
   {                                                                                   \
     int kbc_ = (KBI) < kb1 ? (KBI) : kb1 - 1;                                         \
     kbc_ = kbc_ < 0 ? 0 : kbc_;                                                       \
-    _Pragma("unroll") for (int rt = 0; rt < 4; ++rt)                                  \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                 \
-        const int col_ = kbc_ * 64 + 32 * h + 8 * j;                                  \
-        a[P][rt][j] = *reinterpret_cast<const u32x4_t*>(xrow[rt] + (col_ < M ? col_ : 0)); \
-      }                                                                               \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                   \
+      const int col_ = kbc_ * 64 + 32 * h + 8 * j;                                    \
+      a[P][rt][j] = *reinterpret_cast<const u32x4_t*>(xrow[rt] + (col_ < M ? col_ : 0)); \
+    }                                                                                 \
   }
+  // (two column tiles leave no registers for a pinned schedule: the compiler places the loads)
+#define MOE_GATE_FENCE if (ET == 1) __builtin_amdgcn_sched_barrier(0);
   // Vector loads come back in the order they were issued, so a weight fragment requested
   // just before its MFMA would wait behind every x row requested earlier (HBM latency each
   // time).  The weight fragments of a whole super-block of SB feature blocks are therefore
-  // requested first (they hit in L2), then the x rows, PD blocks ahead of their use.
+  // requested first (they hit in L2), then the x rows, PD blocks ahead of their use.  The
+  // fences keep the compiler from moving the loads to their uses.
   constexpr int SB = 4 / ET;
   for (int sb0 = kb0; sb0 < kb1; sb0 += SB) {
     u32x4_t b[SB][4][ET * 3];
@@ -383,25 +401,33 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
       }
     }
 #pragma unroll
-    for (int p = 0; p < PD; ++p) MOE_GATE_LOAD_X2(p, sb0 + p)
+    for (int p = 0; p < PD; ++p)
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt) MOE_GATE_LOAD_XROW(p, sb0 + p, rt)
+    MOE_GATE_FENCE
 #pragma unroll
     for (int q = 0; q < SB; ++q) {
-      if (sb0 + q < kb1) {                            // wave-uniform
+      const bool live = sb0 + q < kb1;                // wave-uniform
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+      for (int rt = 0; rt < 4; ++rt) {
+        if (live) {
 #pragma unroll
-          for (int t = 0; t < ET; ++t)
+          for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt) {
+            for (int t = 0; t < ET; ++t) {
               acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 2], acc[rt][t]);
               acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 1], acc[rt][t]);
               acc[rt][t] = MOE_GATE_MFMA(a[q % PD][rt][j], b[q][j][t * 3 + 0], acc[rt][t]);
             }
+        }
+        MOE_GATE_FENCE
+        if (q + PD < SB) MOE_GATE_LOAD_XROW(q % PD, sb0 + q + PD, rt)
+        MOE_GATE_FENCE
       }
-      if (q + PD < SB) MOE_GATE_LOAD_X2(q % PD, sb0 + q + PD)
     }
   }
-#undef MOE_GATE_LOAD_X2
+#undef MOE_GATE_LOAD_XROW
+#undef MOE_GATE_FENCE
   // acc[rt][t][i]: token row 32 rt + 8 (i/4) + 4 h + i%4, expert 32 t + r
   float* dst = part + (size_t)wave * 128 * pitch;
 #pragma unroll
@@ -412,15 +438,95 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
       for (int i = 0; i < 16; ++i)
         dst[(32 * rt + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + 32 * t + r] = acc[rt][t][i];
   __syncthreads();
-  for (int i = threadIdx.x; i < 128 * pitch; i += 256)
-    part[i] = (part[i] + part[128 * pitch + i]) + (part[2 * 128 * pitch + i] + part[3 * 128 * pitch + i]);
+
+  // ---- epilogue: logits of experts [EPT sub, EPT sub + EPT) of token tk, in registers
+  float z[EPT];
+  {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    const float* zr = part + (size_t)tk * pitch + EPT * sub;
+#pragma unroll
+    for (int i4 = 0; i4 < EPT / 4; ++i4) {
+      const f32x4_t p0 = *reinterpret_cast<const f32x4_t*>(zr + 4 * i4);
+      const f32x4_t p1 = *reinterpret_cast<const f32x4_t*>(zr + 128 * pitch + 4 * i4);
+      const f32x4_t p2 = *reinterpret_cast<const f32x4_t*>(zr + 2 * 128 * pitch + 4 * i4);
+      const f32x4_t p3 = *reinterpret_cast<const f32x4_t*>(zr + 3 * 128 * pitch + 4 * i4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) z[4 * i4 + k] = (p0[k] + p1[k]) + (p2[k] + p3[k]);
+    }
+  }
+  const int ebase = EPT * sub;
+  Top2 t2{-INFINITY, INT_MAX, -INFINITY, INT_MAX};
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int e = ebase + k;
+    if (e < E) {
+      if (better(z[k], e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z[k]; t2.e1 = e; }
+      else if (better(z[k], e, t2.v2, t2.e2)) { t2.v2 = z[k]; t2.e2 = e; }
+    }
+  }
+  {
+    Top2 other;
+    other.v1 = __shfl_xor(t2.v1, 16, 64); other.e1 = __shfl_xor(t2.e1, 16, 64);
+    other.v2 = __shfl_xor(t2.v2, 16, 64); other.e2 = __shfl_xor(t2.e2, 16, 64);
+    t2 = top2_merge(t2, other);
+  }
+  // softmax numerators (bulk exponentials: the hardware exp2 path, relative error ~1e-6 at most
+  // over the range a softmax tail can reach)
+  float psum = 0.f;
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    z[k] = ebase + k < E ? __expf(z[k] - t2.v1) : 0.f;
+    psum += z[k];
+  }
+  psum += __shfl_xor(psum, 16, 64);
+  const float inv = valid ? 1.0f / psum : 0.f;        // rows past the end of the group count as zeros
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) z[k] *= inv;          // the gates
+  if (gates_opt != nullptr && valid) {
+#pragma unroll
+    for (int k = 0; k < EPT; ++k)
+      if (ebase + k < E) gates_opt[n_ep * E + ebase + k] = z[k];
+  }
+  int* h1 = hh + (wave >> 1) * 2 * Epad;              // the histograms of this wavefront's chunk
+  int* h2 = h1 + Epad;
+  if (sub == 0 && valid) {
+    const float p2 = expf(t2.v2 - t2.v1);
+    const float g1n = 1.0f / (1.0f + p2);
+    const float g2n = p2 / (1.0f + p2);
+    const bool sampled = 2.0f * g2n > u_n;
+    expert_idx[2 * n_ep] = t2.e1;
+    expert_idx[2 * n_ep + 1] = t2.e2;
+    weight[2 * n_ep] = g1n;          // provisional: zeroed later if the slot is lost
+    weight[2 * n_ep + 1] = g2n;
+    slot[2 * n_ep + 1] = sampled ? 0 : MOE_SLOT_NOT_SAMPLED;
+    atomicAdd(&h1[t2.e1], 1);
+    if (sampled) atomicAdd(&h2[t2.e2], 1);
+  }
+  // gate sums over the 32 tokens of the wavefront (butterfly over the lanes with the same half:
+  // a fixed order), then over the two wavefronts of a chunk
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    float v = z[k];
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 8, 64);
+    v += __shfl_xor(v, 32, 64);
+    z[k] = v;
+  }
+  if ((lane & 47) == 0) {
+#pragma unroll
+    for (int k = 0; k < EPT; ++k) msw[wave * Epad + ebase + k] = z[k];
+  }
   __syncthreads();
-#pragma unroll 1
-  for (int c = 0; c < 2; ++c) {
-    const int ch = 2 * pr + c;
-    if (ch < nch)                                     // block-uniform
-      gate_chunk_epilogue<256, Epad>(part + (size_t)c * 64 * pitch, pitch, g, ch, S, E, nch, u, expert_idx,
-                               slot, weight, gates_opt, hist1, hist2, msum, hh, hh + Epad);
+  for (int i = threadIdx.x; i < 2 * Epad; i += 256) {
+    const int c = i / Epad, e = i - c * Epad, ch = 2 * pr + c;
+    if (ch < nch && e < E) {
+      const size_t base = ((size_t)g * nch + ch) * E;
+      msum[base + e] = msw[2 * c * Epad + e] + msw[(2 * c + 1) * Epad + e];
+      hist1[base + e] = hh[c * 2 * Epad + e];
+      hist2[base + e] = hh[c * 2 * Epad + Epad + e];
+    }
   }
 }
 
@@ -1013,7 +1119,8 @@ int launch_gate_pack(const moe_config& c, const float* wg, void* packed, hipStre
   return check_launch();
 }
 
-constexpr size_t kGateRowsLds1 = (4 * 128 * 33 + 2 * 32) * 4, kGateRowsLds2 = (4 * 128 * 65 + 2 * 64) * 4;
+// partial logits [4][128][Epad + 4], per-wavefront gate sums [4][Epad], histograms [4][Epad]
+constexpr size_t kGateRowsLds1 = (4 * 128 * 36 + 8 * 32) * 4, kGateRowsLds2 = (4 * 128 * 68 + 8 * 64) * 4;
 
 int prepare_gate() {
   static LdsLimitOnce once1, once2;
