@@ -218,60 +218,89 @@ __device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
   return r;
 }
 
-// Softmax / top-2 / random routing / chunk statistics for the 64 tokens of one
-// chunk whose logits sit in LDS (zs, row pitch `pitch` floats).  NT threads:
-// TPT = NT/64 per token, expert e handled by thread e % TPT of the token's group.
-// Must be called by all threads of the block; ends with a barrier.
-template <int NT, int EMAX>
+// Softmax / top-2 / random routing / chunk statistics for the 64 tokens of one chunk whose
+// logits sit in LDS (zs, row pitch `pitch` floats, pitch = 8 mod 64).  NT threads, TPT = NT/64
+// per token; a wavefront holds 64/TPT tokens (lane % (64/TPT)) and thread `sub` = lane / (64/TPT)
+// of a token owns the 4-expert groups sub, sub + TPT, ...: its 16-byte reads and those of the
+// 15 lanes around it fall into different banks.  A token's logits are processed in registers
+// and its gates written back for the column sums.  Must be called by all threads of the block;
+// ends with a barrier.
+template <int NT, int EPAD>
 __device__ __forceinline__ void gate_chunk_epilogue(
     float* zs, int pitch, int g, int ch, int S, int E, int nch, const float* __restrict__ u,
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt, int32_t* __restrict__ hist1, int32_t* __restrict__ hist2,
     float* __restrict__ msum, int* h1, int* h2) {
-  constexpr int TPT = NT / 64;
-  __shared__ float rinv[kChunk];
-  __shared__ float mpart[8 * EMAX];
-  const int tid = threadIdx.x;
-  for (int e = tid; e < E; e += NT) { h1[e] = 0; h2[e] = 0; }
-  __syncthreads();
-  const int tk = tid / TPT, sub = tid % TPT;
+  constexpr int TPT = NT / 64, TPW = 64 / TPT, EPT = EPAD / TPT, NG = EPT / 4;
+  static_assert(EPT % 4 == 0 && EPT >= 4, "whole 4-expert groups per thread");
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  __shared__ float mpart[8 * EPAD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tk = wave * TPW + lane % TPW, sub = lane / TPW;
   const int s = ch * kChunk + tk;
   const bool valid = s < S;
   const size_t n = (size_t)g * S + (valid ? s : 0);
+  const float u_n = u[n];                              // needed last: its latency hides below
+  for (int e = tid; e < E; e += NT) { h1[e] = 0; h2[e] = 0; }
   float* zr = zs + (size_t)tk * pitch;
-  Top2 t2{-INFINITY, INT_MAX, -INFINITY, INT_MAX};
-  for (int e = sub; e < E; e += TPT) {
-    const float z = zr[e];
-    if (better(z, e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z; t2.e1 = e; }
-    else if (better(z, e, t2.v2, t2.e2)) { t2.v2 = z; t2.e2 = e; }
-  }
+  float z[EPT];
 #pragma unroll
-  for (int o = 1; o < TPT; o <<= 1) {
+  for (int i = 0; i < NG; ++i) {
+    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(zr + 4 * (sub + TPT * i));
+#pragma unroll
+    for (int k = 0; k < 4; ++k) z[4 * i + k] = v[k];
+  }
+  Top2 t2{-INFINITY, INT_MAX, -INFINITY, INT_MAX};
+#pragma unroll
+  for (int i = 0; i < NG; ++i)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int e = 4 * (sub + TPT * i) + k;
+      const float zv = z[4 * i + k];
+      if (e < E) {
+        if (better(zv, e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = zv; t2.e1 = e; }
+        else if (better(zv, e, t2.v2, t2.e2)) { t2.v2 = zv; t2.e2 = e; }
+      }
+    }
+#pragma unroll
+  for (int o = TPW; o < 64; o <<= 1) {
     Top2 other;
     other.v1 = __shfl_xor(t2.v1, o, 64); other.e1 = __shfl_xor(t2.e1, o, 64);
     other.v2 = __shfl_xor(t2.v2, o, 64); other.e2 = __shfl_xor(t2.e2, o, 64);
     t2 = top2_merge(t2, other);
   }
-  // softmax numerators stay in LDS; the reciprocal of the row sum goes to rinv[] and is
-  // applied when the chunk's gate sums are formed (bulk exponentials: the hardware
-  // exp2 path, relative error ~1e-6 at most over the range a softmax tail can reach)
+  // softmax (bulk exponentials: the hardware exp2 path, relative error ~1e-6 at most over the
+  // range a softmax tail can reach); rows past the end of the group count as zeros
   float psum = 0.f;
-  for (int e = sub; e < E; e += TPT) {
-    const float p = __expf(zr[e] - t2.v1);
-    zr[e] = p;
-    psum += p;
-  }
 #pragma unroll
-  for (int o = 1; o < TPT; o <<= 1) psum += __shfl_xor(psum, o, 64);
-  const float inv = 1.0f / psum;
-  if (sub == 0) rinv[tk] = valid ? inv : 0.f;
-  if (gates_opt != nullptr && valid)
-    for (int e = sub; e < E; e += TPT) gates_opt[n * E + e] = zr[e] * inv;
+  for (int i = 0; i < NG; ++i)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float p = 4 * (sub + TPT * i) + k < E ? __expf(z[4 * i + k] - t2.v1) : 0.f;
+      z[4 * i + k] = p;
+      psum += p;
+    }
+#pragma unroll
+  for (int o = TPW; o < 64; o <<= 1) psum += __shfl_xor(psum, o, 64);
+  const float inv = valid ? 1.0f / psum : 0.f;
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    f32x4_t v;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = z[4 * i + k] * inv;
+    *reinterpret_cast<f32x4_t*>(zr + 4 * (sub + TPT * i)) = v;
+    if (gates_opt != nullptr && valid) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (4 * (sub + TPT * i) + k < E) gates_opt[n * E + 4 * (sub + TPT * i) + k] = v[k];
+    }
+  }
+  __syncthreads();                                     // histograms cleared, gates in LDS
   if (sub == 0 && valid) {
     const float p2 = expf(t2.v2 - t2.v1);
     const float g1n = 1.0f / (1.0f + p2);
     const float g2n = p2 / (1.0f + p2);
-    const bool sampled = 2.0f * g2n > u[n];
+    const bool sampled = 2.0f * g2n > u_n;
     expert_idx[2 * n] = t2.e1;
     expert_idx[2 * n + 1] = t2.e2;
     weight[2 * n] = g1n;            // provisional: zeroed later if the slot is lost
@@ -280,11 +309,10 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     atomicAdd(&h1[t2.e1], 1);
     if (sampled) atomicAdd(&h2[t2.e2], 1);
   }
-  __syncthreads();
   const size_t base = ((size_t)g * nch + ch) * E;
   // Gate sums of the chunk in a fixed order: eight interleaved partial sums over the 64 rows
-  // (partial q takes rows q, q + 8, ...; rows past the end of the group carry rinv = 0), then a
-  // tree.  tpe = 8, 4, 2 or 1 threads share the partial sums of one expert.
+  // (partial q takes rows q, q + 8, ...), then a tree.  tpe = 8, 4, 2 or 1 threads share the
+  // partial sums of one expert.
   int tpe = 8;
   while (tpe * E > NT) tpe >>= 1;
   {
@@ -293,7 +321,7 @@ __device__ __forceinline__ void gate_chunk_epilogue(
       for (int q = j; q < 8; q += tpe) {
         float part = 0.f;
 #pragma unroll
-        for (int r0 = 0; r0 < kChunk; r0 += 8) part = fmaf(zs[(size_t)(r0 + q) * pitch + e], rinv[r0 + q], part);
+        for (int r0 = 0; r0 < kChunk; r0 += 8) part += zs[(size_t)(r0 + q) * pitch + e];
         mpart[8 * e + q] = part;
       }
   }
@@ -540,7 +568,7 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int NT = 64 * NW, T = ETW * NW, Epad = 32 * T, pitch = Epad + 1;
+  constexpr int NT = 64 * NW, T = ETW * NW, Epad = 32 * T, pitch = Epad + 8;   // 8 mod 64: see the epilogue
   constexpr int AV = 1024 / NT;                        // 16-byte vectors of x per thread and block
   constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
   constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
@@ -670,7 +698,7 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
     int32_t* __restrict__ expert_idx, int32_t* __restrict__ slot, float* __restrict__ weight,
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
-  constexpr int NW = 4, NT = 512, T = ETW * NW, Epad = 32 * T, pitch = Epad + 1;
+  constexpr int NW = 4, NT = 512, T = ETW * NW, Epad = 32 * T, pitch = Epad + 8;   // 8 mod 64: see the epilogue
   constexpr int AV = 4, RD = 8;                        // loader: 16-byte vectors per thread and block
   constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
   constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
@@ -820,14 +848,30 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(
   const int seg = (nch + 7) / 8;
   const int ch0 = k * seg, ch1 = (ch0 + seg < nch) ? ch0 + seg : nch;
   const bool live = e < E;
+  // the loads of a batch of UN chunks are independent (one memory latency per batch); a segment
+  // that fits one batch stays in registers for the second pass
+  constexpr int UN = 8;
+  const bool single = seg <= UN;
+  int a1[UN], a2[UN];
   int s1 = 0, s2 = 0;
   float ms = 0.f;
   if (live)
-    for (int ch = ch0; ch < ch1; ++ch) {
-      const size_t i = ((size_t)g * nch + ch) * E + e;
-      s1 += hist1[i];
-      s2 += hist2[i];
-      ms += msum[i];
+    for (int c0 = ch0; c0 < ch1; c0 += UN) {
+      float am[UN];
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        const bool in = c0 + j < ch1;
+        const size_t i = ((size_t)g * nch + (in ? c0 + j : ch0)) * E + e;
+        a1[j] = in ? hist1[i] : 0;
+        a2[j] = in ? hist2[i] : 0;
+        am[j] = in ? msum[i] : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        s1 += a1[j];
+        s2 += a2[j];
+        if (c0 + j < ch1) ms += am[j];                // chunk order, as a plain loop would add
+      }
     }
   t1[k][threadIdx.x & 31] = s1;
   t2[k][threadIdx.x & 31] = s2;
@@ -845,10 +889,23 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(
     mtot += tm[kk][threadIdx.x & 31];
   }
   int run1 = base1, run2 = base2 + tot1;
-  for (int ch = ch0; ch < ch1; ++ch) {
-    const size_t i = ((size_t)g * nch + ch) * E + e;
-    const int a = hist1[i]; hist1[i] = run1; run1 += a;
-    const int b = hist2[i]; hist2[i] = run2; run2 += b;
+  for (int c0 = ch0; c0 < ch1; c0 += UN) {
+    if (!single) {
+#pragma unroll
+      for (int j = 0; j < UN; ++j) {
+        const bool in = c0 + j < ch1;
+        const size_t i = ((size_t)g * nch + (in ? c0 + j : ch0)) * E + e;
+        a1[j] = in ? hist1[i] : 0;
+        a2[j] = in ? hist2[i] : 0;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < UN; ++j)
+      if (c0 + j < ch1) {
+        const size_t i = ((size_t)g * nch + c0 + j) * E + e;
+        hist1[i] = run1; run1 += a1[j];
+        hist2[i] = run2; run2 += a2[j];
+      }
   }
   const long long tot = (long long)tot1 + tot2;
   const int f = tot < C ? (int)tot : C;
@@ -928,15 +985,17 @@ __global__ __launch_bounds__(64) void gate_slots_kernel(
       if (cb >= 0) rb2 += fill[(size_t)gg * E + cb];
     }
   }
-  int r1 = 0, r2 = 0;
-  for (int i = 0; i < kChunk - 1; ++i) {
-    const int o1 = __shfl(e1, i, 64);
-    const int o2 = __shfl(e2, i, 64);
-    if (i < lane) {
-      r1 += (o1 == e1);
-      r2 += (o2 == e2);
-    }
+  // stable rank among the earlier tokens of the chunk with the same expert: the lanes that agree
+  // with this one in every bit of the expert index, one ballot per bit
+  unsigned long long peers1 = __ballot(e1 >= 0), peers2 = __ballot(e2 >= 0);
+  for (int bit = 0; (E - 1) >> bit; ++bit) {
+    const bool b1 = (e1 >> bit) & 1, b2 = (e2 >> bit) & 1;
+    const unsigned long long m1 = __ballot(b1), m2 = __ballot(b2);
+    peers1 &= b1 ? m1 : ~m1;
+    peers2 &= b2 ? m2 : ~m2;
   }
+  const unsigned long long earlier = (1ull << lane) - 1;
+  const int r1 = __popcll(peers1 & earlier), r2 = __popcll(peers2 & earlier);
   if (packing && rb_shared) {
     rb_s[lane] = rb1;
     rb_s[lane + 64] = rb2;
