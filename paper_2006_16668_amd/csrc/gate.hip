@@ -691,7 +691,10 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_cols_kernel(
 // block waits for that block's HBM latency; split by role, the multiplying wavefronts only wait
 // for L2.  The loader wavefronts keep a ring of RD feature blocks in flight (global -> registers
 // -> LDS stage); both roles pass the same barriers, one per 64-feature block.
-template <int ETW, int PB, int RB>   // RB: ring of B register sets (power of two), PB < RB steps ahead
+// RT 32-token row tiles per block (4 or 8): with 256 tokens a weight fragment from L2 feeds 8 MFMA
+// groups instead of 4, i.e. half the L2 traffic per token (one column tile per wavefront only:
+// the accumulators of 8 x 2 tiles would fill the register file).
+template <int ETW, int PB, int RB, int RT = 4>   // RB: ring of B register sets (power of two), PB < RB steps ahead
 __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
     const bf16_t* __restrict__ x, const uint4* __restrict__ wgP, const float* __restrict__ u,
     int S, int M, int E, int nch,
@@ -699,9 +702,10 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
     float* __restrict__ gates_opt,
     int32_t* __restrict__ hist1, int32_t* __restrict__ hist2, float* __restrict__ msum) {
   constexpr int NW = 4, NT = 512, T = ETW * NW, Epad = 32 * T, pitch = Epad + 8;   // 8 mod 64: see the epilogue
-  constexpr int AV = 4, RD = 8;                        // loader: 16-byte vectors per thread and block
+  constexpr int ROWS = 32 * RT, CPB = RT / 2;          // tokens and chunks per block
+  constexpr int AV = RT, RD = 32 / RT;                 // loader: 16-byte vectors per thread and block, ring depth
   constexpr int kAPitch = 72;                          // 64 + 8 bf16: 16-byte pad
-  constexpr int kABytes = 2 * 128 * kAPitch * 2;       // two stages
+  constexpr int kABytes = 2 * ROWS * kAPitch * 2;      // two stages
   constexpr int kZBytes = 64 * pitch * 4;              // logits of one chunk
   constexpr int kUnion = kABytes > kZBytes ? kABytes : kZBytes;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kUnion];
@@ -710,29 +714,29 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
   float* zs = reinterpret_cast<float*>(smem);
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-  const int npair = (nch + 1) / 2;
+  const int npair = (nch + CPB - 1) / CPB;
   const int g = blockIdx.x / npair, pr = blockIdx.x % npair;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, h = lane >> 5;
   const int KB = (M + 63) / 64;
 
-  f32x16_t acc[4][ETW];
+  f32x16_t acc[RT][ETW];
 #pragma unroll
-  for (int rt = 0; rt < 4; ++rt)
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int t = 0; t < ETW; ++t)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rt][t][i] = 0.f;
 
   if (wave >= NW) {
-    // ---- loader wavefronts: 128 rows x 64 features = 1024 16-byte vectors per feature block;
+    // ---- loader wavefronts: ROWS rows x 64 features = 8 ROWS 16-byte vectors per feature block;
     // rows past S are clamped (never used), features past M read the row start (zero weights)
     const int lt = tid - 64 * NW, lrow = lt >> 3, lvec = lt & 7;   // rows lrow + 32 i
     const bf16_t* xrow[AV];
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-      int s = pr * 128 + lrow + 32 * i;
+      int s = pr * ROWS + lrow + 32 * i;
       s = s < S ? s : S - 1;
       xrow[i] = x + ((size_t)g * S + s) * M;
     }
@@ -745,7 +749,7 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
   }
 #define MOE_GATE_STORE_A(P, buf)                                                         \
   _Pragma("unroll") for (int i = 0; i < AV; ++i)                                         \
-    *reinterpret_cast<u32x4_t*>(As + (buf) * 128 * kAPitch + (lrow + 32 * i) * kAPitch + lvec * 8) = areg[P][i];
+    *reinterpret_cast<u32x4_t*>(As + (buf) * ROWS * kAPitch + (lrow + 32 * i) * kAPitch + lvec * 8) = areg[P][i];
     MOE_GATE_LOAD_A(0, 0)
 #pragma unroll
     for (int p = 1; p < RD; ++p) MOE_GATE_LOAD_A(p, p)
@@ -786,22 +790,21 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
       for (int ku = 0; ku < KU; ++ku) {
         const int kb = kb0 + ku;
         if (kb < KB) {                                  // block-uniform
-          const bf16_t* as = As + (kb & 1) * 128 * kAPitch + r * kAPitch + 32 * h;
+          const bf16_t* as = As + (kb & 1) * ROWS * kAPitch + r * kAPitch + 32 * h;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             MOE_GATE_LOAD_B((4 * ku + j + PB) % RB, kb * 4 + j + PB)
-            u32x4_t af[4];
+            u32x4_t af[RT];
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt)
+            for (int rt = 0; rt < RT; ++rt)
               af[rt] = *reinterpret_cast<const u32x4_t*>(as + rt * 32 * kAPitch + 8 * j);
 #pragma unroll
             for (int t = 0; t < ETW; ++t)
 #pragma unroll
-              for (int rt = 0; rt < 4; ++rt) {
-                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 2], acc[rt][t]);
-                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 1], acc[rt][t]);
-                acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + 0], acc[rt][t]);
-              }
+              for (int sp = 2; sp >= 0; --sp)           // smallest term first; RT independent MFMAs in a row
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+                  acc[rt][t] = MOE_GATE_MFMA(af[rt], bq[(4 * ku + j) % RB][t * 3 + sp], acc[rt][t]);
           }
           __syncthreads();
         }
@@ -810,23 +813,24 @@ __global__ __launch_bounds__(512) void gate_mfma_cols_split_kernel(
 #undef MOE_GATE_LOAD_B
   }
   // the A stages are dead from here on; the same LDS holds one chunk of logits at a time
-#pragma unroll 1
-  for (int c = 0; c < 2; ++c) {
-    const int ch = pr * 2 + c;
-    if (ch >= nch) break;                              // block-uniform
-    if (wave < NW) {
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr)
+  for (int c = 0; c < CPB; ++c) {
+    const int ch = pr * CPB + c;
+    if (ch < nch) {                                    // block-uniform
+      if (wave < NW) {
 #pragma unroll
-        for (int t = 0; t < ETW; ++t)
+        for (int rr = 0; rr < 2; ++rr)
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
-                c == 0 ? acc[rr][t][i] : acc[2 + rr][t][i];
+          for (int t = 0; t < ETW; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              zs[(rr * 32 + 8 * (i >> 2) + 4 * h + (i & 3)) * pitch + (wave * ETW + t) * 32 + r] =
+                  acc[2 * c + rr][t][i];
+      }
+      __syncthreads();
+      gate_chunk_epilogue<NT, Epad>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
+                              hist1, hist2, msum, hh, hh + Epad);
     }
-    __syncthreads();
-    gate_chunk_epilogue<NT, Epad>(zs, pitch, g, ch, S, E, nch, u, expert_idx, slot, weight, gates_opt,
-                            hist1, hist2, msum, hh, hh + Epad);
   }
 }
 #undef MOE_GATE_MFMA
@@ -1246,7 +1250,16 @@ int launch_gate(const moe_config& c, const void* x, const float* wg, const float
       if (c.E <= 32) hipLaunchKernelGGL(gate_mfma_rows_kernel<1>, grid, block, lds1, st, MOE_GATE_ARGS);
       else hipLaunchKernelGGL(gate_mfma_rows_kernel<2>, grid, block, lds2, st, MOE_GATE_ARGS);
     }
-    else if (c.E <= 128) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 6, 8>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    else if (c.E <= 128) {
+      // 256-token blocks once they give every compute unit a block
+      int cus = 0;
+      if (compute_units(&cus) != MOE_OK) return MOE_EHIP;
+      const long long blocks256 = (long long)c.G * ((nch + 3) / 4);
+      if (blocks256 >= cus)
+        hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 6, 8, 8>), dim3((unsigned)blocks256), dim3(512), 0, st, MOE_GATE_ARGS);
+      else
+        hipLaunchKernelGGL((gate_mfma_cols_split_kernel<1, 6, 8>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
+    }
     else if (c.E <= 256) hipLaunchKernelGGL((gate_mfma_cols_split_kernel<2, 2, 4>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
     else hipLaunchKernelGGL((gate_mfma_cols_kernel<2, 8, 2>), grid, dim3(512), 0, st, MOE_GATE_ARGS);
 #undef MOE_GATE_ARGS

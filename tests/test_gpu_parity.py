@@ -64,6 +64,11 @@ SMALL_CASES = [
     # fp32 rows need 16 bytes = 4 elements only
     MoEConfig("f32_quads", G=3, S=90, M=36, H=44, E=5, C=21, act_dtype="f32", seed=48),
     MoEConfig("gather_wrap", G=8, S=400, M=128, H=2048, E=40, C=32, act_dtype="bf16", seed=33),
+    # 64 < E <= 128 with enough tokens for the 256-token blocks of the gate (one block per compute
+    # unit): blocks whose last chunks are ragged or missing, a feature count that is no multiple
+    # of 64
+    MoEConfig("e100_blocks256", G=256, S=130, M=72, H=32, E=100, C=3, act_dtype="bf16", seed=49),
+    MoEConfig("e128_blocks256", G=128, S=300, M=128, H=32, E=128, C=5, act_dtype="bf16", seed=50),
     # the layer call packs the occupied rows of an expert to the front of its block and multiplies
     # only the 256-row tiles that hold them: skewed routing (full and nearly empty experts), far
     # more capacity than tokens (one tile of several per expert), experts that receive nothing,
