@@ -257,9 +257,9 @@ __device__ __forceinline__ void gate_chunk_epilogue(
     for (int k = 0; k < 4; ++k) {
       const int e = 4 * (sub + TPT * i) + k;
       const float zv = z[4 * i + k];
-      if (e < E) {
-        if (better(zv, e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = zv; t2.e1 = e; }
-        else if (better(zv, e, t2.v2, t2.e2)) { t2.v2 = zv; t2.e2 = e; }
+      if (e < E) {   // a thread meets its experts in ascending order: strict > keeps the lowest index of a tie
+        if (zv > t2.v1) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = zv; t2.e1 = e; }
+        else if (zv > t2.v2) { t2.v2 = zv; t2.e2 = e; }
       }
     }
 #pragma unroll
@@ -487,9 +487,9 @@ __global__ __launch_bounds__(256) void gate_mfma_rows_kernel(
 #pragma unroll
   for (int k = 0; k < EPT; ++k) {
     const int e = ebase + k;
-    if (e < E) {
-      if (better(z[k], e, t2.v1, t2.e1)) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z[k]; t2.e1 = e; }
-      else if (better(z[k], e, t2.v2, t2.e2)) { t2.v2 = z[k]; t2.e2 = e; }
+    if (e < E) {     // ascending order: strict > keeps the lowest index of a tie
+      if (z[k] > t2.v1) { t2.v2 = t2.v1; t2.e2 = t2.e1; t2.v1 = z[k]; t2.e1 = e; }
+      else if (z[k] > t2.v2) { t2.v2 = z[k]; t2.e2 = e; }
     }
   }
   {
