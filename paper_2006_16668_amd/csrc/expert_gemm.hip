@@ -326,10 +326,7 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
   // about 8 row tiles x 4 column tiles, the split that shares the most operand panels in that
   // XCD's L2 (a tall output, as in the weight gradients, would otherwise re-read its A panel
   // once per column tile).
-#ifndef MOE_DMA_KBAND
-#define MOE_DMA_KBAND 8
-#endif
-  constexpr int kBand = MOE_DMA_KBAND;
+  constexpr int kBand = 8;   // bands of 2 or 4 row tiles measured the same on the forward shapes
   // PACKED: kept_s[e] = occupied rows of expert e, rts_s[e] = occupied row tiles of the experts
   // before e (rts_s[E] = all of them), behind the stages and the token / bit areas in LDS
   int* const kept_s = reinterpret_cast<int*>(smem_raw + SM::kBytes + (GATHER ? 1024 : 0) + (EPI == 5 ? 8192 : 0));

@@ -14,10 +14,12 @@
 // bf16 activations take the MFMA form of the first kernel (gate_mfma_*): x is
 // exactly bf16, so with wg split into three bf16 terms (hi + mid + lo = all 24
 // mantissa bits) every product is exact in fp32 and only the accumulation order
-// differs from a plain fp32 dot product.  wg is repacked once per call into the
-// lane order of the v_mfma_f32_32x32x16_bf16 B operand, so each B load is one
-// contiguous 1 KB read.  fp32 activations (and very wide gates) keep the plain
-// FMA kernel.
+// differs from a plain fp32 dot product.  wg is repacked (by the caller once per
+// weight update, else once per call) into the lane order of the
+// v_mfma_f32_32x32x16_bf16 B operand, so each B load is one contiguous 1 KB read.
+// Gates wider than 512 experts and fp32 activations with GEMM-friendly shapes get
+// their logits from the persistent GEMM kernel; everything else keeps the plain FMA
+// kernel.
 //
 // Positions never come from atomics: they are exact counts of earlier tokens, so
 // the result equals the sequential two-pass loop of Algorithm 1 bit for bit.
