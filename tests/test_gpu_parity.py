@@ -69,6 +69,8 @@ SMALL_CASES = [
     # of 64
     MoEConfig("e100_blocks256", G=256, S=130, M=72, H=32, E=100, C=3, act_dtype="bf16", seed=49),
     MoEConfig("e128_blocks256", G=128, S=300, M=128, H=32, E=128, C=5, act_dtype="bf16", seed=50),
+    # more than 64 chunks per group: the scan over the chunks walks its segments in several batches
+    MoEConfig("long_group", G=2, S=4250, M=32, H=16, E=6, C=700, act_dtype="bf16", seed=51),
     # the layer call packs the occupied rows of an expert to the front of its block and multiplies
     # only the 256-row tiles that hold them: skewed routing (full and nearly empty experts), far
     # more capacity than tokens (one tile of several per expert), experts that receive nothing,
