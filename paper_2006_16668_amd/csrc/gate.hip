@@ -924,12 +924,6 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(
   for (int c = f + k; c < C; c += 8) st[c] = -1;
 }
 
-__device__ __forceinline__ int wave_sum_int(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-
 // One wavefront per chunk.  pk.packed_src != NULL: also builds the packed row layout of the
 // expert GEMMs (row of a kept choice = kept rows of the same expert in earlier groups + slot).
 __global__ __launch_bounds__(64) void gate_slots_kernel(
