@@ -568,10 +568,14 @@ __global__ __launch_bounds__(256) void expert_gemm_bf16_dma_kernel(
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < c_steps; ++kt, ++g) {
+      // (a fragment row's reads go out right before the MFMA row of the other k half: pinned,
+      // it measures 0.6-0.8 % faster than leaving the order to the compiler)
 #pragma unroll
-      for (int i = 0; i < TM; ++i) { MOE_DMA_READ_A(fr[1], stage, 1, i) MOE_DMA_READ_B(fr[1], stage, 1, i) }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) { MOE_DMA_MFMA_ROW(fr[0], i) }
+      for (int i = 0; i < TM; ++i) {
+        MOE_DMA_READ_A(fr[1], stage, 1, i) MOE_DMA_READ_B(fr[1], stage, 1, i)
+        MOE_DMA_MFMA_ROW(fr[0], i)
+        __builtin_amdgcn_sched_barrier(0);
+      }
       // The own copies of step g+1 must have landed; younger steps (8 copies each) may
       // still fly.  p_g steps have been started.  Copies land in the order they were issued,
       // but stores complete in no fixed order relative to them: "at most n operations
